@@ -1,0 +1,94 @@
+// Internal declarations shared by the host packer, the C ABI glue and the HIP kernels.
+// Not part of the public interface (see include/spmm.h).
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "spmm.h"
+
+namespace spmm {
+
+// ---------------------------------------------------------------------------------------
+// Device layout: "row-tile union" format.
+//
+// The weight is cut into row tiles of TILE_ROWS = 16 output rows (four 4x1 block-rows in
+// the paper's orientation).  For each row tile and each K segment of `kc` consecutive k,
+// the k positions at which ANY of the 16 rows is non-zero are listed; the list is padded
+// to a multiple of STEP_K = 64 and cut into steps.  One step is exactly one
+// v_mfma_i32_16x16x64_i8: 16 rows x 64 listed k, stored dense (zero where a row has no
+// block at that k) in the register layout of the weight operand:
+//     vals[step][lane][t] = W[16*tile + (lane % 16)][ k_list[16*(lane / 16) + t] ],  t < 16
+// so a wave fetches a step with one coalesced 16-byte load per lane.  The matching
+// activation rows are named by segment-local indices, stored pairwise so that the lane that
+// supplies the LDS address of list slot 16g+t (first transposing read) and 16g+8+t (second)
+// finds both in one dword:
+//     idx[step][8*g + t] = k_local[16g + t] | k_local[16g + 8 + t] << 16,   g < 4, t < 8
+// Padding slots carry zero weights and index 0 (always resident), so they add nothing.
+// ---------------------------------------------------------------------------------------
+constexpr int TILE_ROWS = 16;
+constexpr int STEP_K = 64;
+constexpr int STEP_VAL_BYTES = TILE_ROWS * STEP_K;   // 1024
+constexpr int STEP_IDX_DWORDS = STEP_K / 2;          // 32
+constexpr int SEGMENT_ROWS = 1024;                   // kc: activation rows resident in LDS at once
+
+struct HostLayout {
+    int kc = 0, nseg = 0, ntiles = 0;
+    int64_t nsteps = 0;
+    int max_steps_per_tile = 0;
+    std::vector<uint8_t> vals;      // nsteps * 1024
+    std::vector<uint32_t> idx;      // nsteps * 32
+    std::vector<int32_t> seg_ptr;   // ntiles * nseg + 1
+    std::vector<int32_t> rowsum;    // ntiles * 16
+};
+
+// Canonical 4x1 block-sparse-row form (host): what spmm_unpack and spmm_info read.
+struct Bsr {
+    int64_t N = 0, K = 0;
+    spmm_block_t block = SPMM_BLOCK_N4K1;
+    int64_t block_rows = 0;             // ceil(N/4) (N4K1) or N (N1K4)
+    std::vector<int64_t> row_ptr;       // block_rows + 1
+    std::vector<int32_t> index;         // k (N4K1) or K-block c (N1K4), ascending per block-row
+    std::vector<int8_t> vals;           // 4 per block
+};
+
+void bsr_from_dense(const int8_t* W, int64_t N, int64_t K, int64_t ldw, spmm_block_t block, Bsr& out);
+void bsr_to_dense(const Bsr& b, int8_t* W, int64_t ldw);
+void layout_from_bsr(const Bsr& b, int kc, HostLayout& out);
+
+// ---------------------------------------------------------------------------------------
+// Kernel launch interface (implemented in spmm_kernels.hip).
+// ---------------------------------------------------------------------------------------
+struct KernelArgs {
+    const uint8_t* vals;
+    const uint32_t* idx;
+    const int32_t* seg_ptr;
+    const int32_t* rowsum;
+    const uint8_t* X;
+    void* out;
+    const float* w_scale;
+    const float* bias;
+    const int8_t* lut;
+    int64_t ldx, ldo;
+    int N, K, M;
+    int kc, nseg, ntiles;
+    int n_tok_tiles, n_row_groups;
+    int corr_mul;        // 128 - x_zero_point: the activations are multiplied as (x - 128)
+    float x_scale, inv_out, inv_mid, out_zp_f;
+    int x_vec_ok;        // X base 16-byte aligned and ldx % 16 == 0
+    int out_vec_ok;      // out base 16-byte aligned and row pitch a multiple of 16 bytes
+};
+
+struct Plan {
+    int token_tile;      // TM
+    int row_tiles_per_wave;  // R
+    int waves;           // NW
+    int64_t workgroups;
+};
+
+bool plan_supported(int token_tile, int row_tiles_per_wave);
+Plan make_plan(int64_t N, int64_t K, int64_t M, int ntiles, spmm_out_t out_type, int force_tm, int force_r);
+// Launches the SpMM kernel; returns a hipError_t value as int (0 = success).
+int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_postop_t postop, void* stream);
+
+}  // namespace spmm

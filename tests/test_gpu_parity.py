@@ -1,0 +1,277 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs.  Bars: int32 / int8 / uint8 outputs bit-exact; fp32 without GELU
+bit-equal (same fused multiply-add); fp32 with GELU |gpu - ref| <= 1e-5*|ref| + 1e-7
+(two different erfc implementations; the absolute term covers the cancelling tail).
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2306_16601_amd as sp
+import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+GUARD = 64          # poisoned elements before and after the output buffer
+POISON = {"s32": 0x5A5A5A5A, "f32": 12345.678, "s8": 0x5A, "u8": 0xA5}
+TORCH_DT = {"s32": torch.int32, "f32": torch.float32, "s8": torch.int8, "u8": torch.uint8}
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_spmm(W, X, d, case, ldx=None, ldo=None, tuning=None, stream=None, x_offset=0, out_offset=0):
+    """Pack W, run the library on device copies of the inputs, return (out, guards_ok)."""
+    N, K = W.shape
+    M = X.shape[1]
+    ldx = ldx or M
+    ldo = ldo or M
+    h = sp.spmm_pack(W, case.orientation)
+    try:
+        if tuning:
+            sp.spmm_set_tuning(h, *tuning)
+        Xbuf = torch.zeros(K * ldx + x_offset + 16, dtype=torch.uint8, device="cuda")
+        Xv = Xbuf[x_offset:x_offset + K * ldx].view(K, ldx)
+        Xv[:, :M] = dev(X)
+        if ldx > M:
+            Xv[:, M:] = 0xEE                                   # must never influence the result
+        ot = case.out_type
+        total = N * ldo + 2 * GUARD + out_offset
+        obuf = torch.full((total,), POISON[ot], dtype=TORCH_DT[ot], device="cuda")
+        oview = obuf[GUARD + out_offset:GUARD + out_offset + N * ldo].view(N, ldo)
+        lut = None
+        if case.postop == "gelu" and ot in ("s8", "u8"):
+            lut = dev(sp.spmm_make_gelu_lut(d["mid_scale"], d["out_scale"], d["out_zero_point"], ot))
+        w_scale = dev(d["w_scale"]) if d.get("w_scale") is not None else None
+        bias = dev(d["bias"]) if d.get("bias") is not None else None
+        ep = sp.make_epilogue(w_scale, d["x_scale"], d["x_zero_point"], bias, case.postop, ot,
+                              d["out_scale"], d["out_zero_point"], d["mid_scale"], lut)
+        st = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
+        sp.spmm_run(h, Xv, M, ldx, ep, oview, ldo, st)
+        torch.cuda.synchronize()
+        out = oview[:, :M].cpu().numpy()
+        full = obuf.cpu().numpy()
+        poison = np.array(POISON[ot]).astype(full.dtype)
+        guards_ok = (full[:GUARD + out_offset] == poison).all() and (full[GUARD + out_offset + N * ldo:] == poison).all()
+        if ldo > M:
+            guards_ok = guards_ok and (oview[:, M:].cpu().numpy() == poison).all()
+        return out, bool(guards_ok)
+    finally:
+        sp.spmm_destroy(h)
+
+
+def oracle_spmm(W, X, d, case):
+    return oracle.spmm(W, X, d["w_scale"], d["x_scale"], d["bias"], case.postop, case.out_type,
+                       d["out_scale"], d["out_zero_point"], d["mid_scale"], d["x_zero_point"])
+
+
+def assert_parity(got, ref, case):
+    assert got.shape == ref.shape and got.dtype == ref.dtype
+    if case.out_type == "f32" and case.postop == "gelu":
+        err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+        tol = 1e-5 * np.abs(ref.astype(np.float64)) + 1e-7
+        bad = err > tol
+        assert not bad.any(), "fp32 GELU: %d of %d outside 1e-5 rel + 1e-7 abs, worst %g" % (
+            bad.sum(), bad.size, (err / tol).max())
+    elif case.out_type == "f32":
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), "fp32 outputs differ bitwise"
+    else:
+        neq = got != ref
+        assert not neq.any(), "%d of %d outputs differ (first at %s)" % (
+            neq.sum(), neq.size, np.argwhere(neq)[0] if neq.any() else None)
+
+
+def check_case(case, **kw):
+    d = wl.make(case)
+    got, guards_ok = gpu_spmm(d["W"], d["X"], d, case, **kw)
+    ref = oracle_spmm(d["W"], d["X"], d, case)
+    assert guards_ok, "write outside the output extent"
+    assert_parity(got, ref, case)
+    return got
+
+
+# ---------------------------------------------------------------------------- configs 1-4
+@pytest.mark.parametrize("orient", [wl.N4K1, wl.N1K4])
+def test_config1_tiny(orient):
+    check_case(wl.tiny_cases(orient)[0])
+
+
+@pytest.mark.parametrize("orient", [wl.N4K1, wl.N1K4])
+def test_config2_mini_ffn_pair(orient):
+    for case in wl.mini_cases(orient):
+        check_case(case)
+
+
+@pytest.mark.parametrize("case", wl.base_cases(batches=(1,)), ids=lambda c: c.name)
+def test_config3_base_sweep_m128(case):
+    check_case(case)
+
+
+@pytest.mark.parametrize("case", [c for c in wl.base_cases(batches=(8, 32), sparsities=(0.7, 0.9))],
+                         ids=lambda c: c.name)
+def test_config3_base_larger_batches(case):
+    check_case(case)
+
+
+@pytest.mark.parametrize("case", wl.large_cases(), ids=lambda c: c.name)
+def test_config4_large_full_size(case):
+    check_case(case)
+
+
+def test_config4_large_both_tunings_agree_bitwise():
+    case = wl.large_cases()[0]
+    d = wl.make(case)
+    a, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=(64, 1))
+    b, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=(64, 2))
+    assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------------------- config 5 (sample of the grid)
+def _grid_sample():
+    allc = wl.grid_cases(out_type="s32")
+    picks = [c for c in allc if (c.N, c.K, c.M) in {
+        (256, 256, 128), (512, 256, 384), (256, 1024, 1024), (768, 768, 384), (1024, 4096, 128),
+        (2048, 512, 384), (3072, 768, 128), (4096, 4096, 128), (768, 3072, 1024), (2048, 2048, 384)}]
+    return [c for c in picks if c.sparsity in (0.7, 0.8, 0.9)]
+
+
+@pytest.mark.parametrize("case", _grid_sample(), ids=lambda c: c.name)
+def test_config5_grid_sample_s32_and_s8(case):
+    check_case(case)
+    check_case(case.with_(out_type="s8"))
+
+
+# ---------------------------------------------------------------------------- edge cases
+@pytest.mark.parametrize("N,K,M", [
+    (1, 1, 1), (3, 5, 2), (4, 4, 4), (17, 33, 65), (50, 70, 130), (130, 1025, 63), (16, 2049, 100),
+    (260, 100, 257), (5, 3000, 7),
+])
+@pytest.mark.parametrize("out_type", ["s32", "s8"])
+def test_ragged_shapes(N, K, M, out_type):
+    case = wl.Case("ragged", N, K, M, 0.6, wl.N4K1, out_type, "none", keys=(60, N, K, M))
+    check_case(case)
+    check_case(case.with_(orientation=wl.N1K4))
+
+
+@pytest.mark.parametrize("out_type,postop", [("s32", "none"), ("f32", "none"), ("f32", "gelu"),
+                                             ("s8", "none"), ("u8", "none"), ("s8", "gelu"), ("u8", "gelu")])
+def test_every_epilogue_with_unaligned_leading_dims(out_type, postop):
+    case = wl.Case("ep", 70, 300, 90, 0.8, wl.N4K1, out_type, postop, keys=(61, 70, 300, 90),
+                   out_zero_point=(3 if postop == "none" and out_type in ("s8", "u8") else 0))
+    check_case(case)                                   # aligned, ragged tail
+    check_case(case, ldx=101, ldo=93)                  # odd pitches: byte paths
+    check_case(case, ldx=112, ldo=96, x_offset=3, out_offset=1)   # misaligned bases
+
+
+def test_without_bias_and_with_activation_zero_point():
+    case = wl.Case("nobias", 64, 256, 128, 0.8, wl.N4K1, "f32", "none", with_bias=False, keys=(62,))
+    check_case(case)
+    case = wl.Case("xzp", 64, 256, 128, 0.8, wl.N4K1, "s32", "none", x_zero_point=37, keys=(63,))
+    check_case(case)
+    check_case(case.with_(out_type="s8", x_zero_point=128))
+
+
+def test_degenerate_weights():
+    K, M = 128, 96
+    X = wl.activations(K, M, keys=(64,))
+    case = wl.Case("deg", 32, K, M, 0.0, wl.N4K1, "f32", "none", keys=(64,))
+    d = wl.make(case)
+    # all-zero W: bias only
+    d["W"] = np.zeros((32, K), np.int8)
+    got, ok = gpu_spmm(d["W"], X, d, case)
+    assert ok and np.array_equal(got, np.repeat(d["bias"][:, None], M, axis=1))
+    # empty block-rows next to fully dense rows, extreme values
+    W = np.zeros((32, K), np.int8)
+    W[4:8] = -128
+    W[12:16] = 127
+    W[20] = 1
+    d["W"] = W
+    Xmax = np.full((K, M), 255, np.uint8)
+    for c in (case.with_(out_type="s32"), case.with_(out_type="s8")):
+        got, ok = gpu_spmm(W, Xmax, d, c)
+        assert ok
+        assert_parity(got, oracle_spmm(W, Xmax, d, c), c)
+    got, _ = gpu_spmm(W, Xmax, d, case.with_(out_type="s32"))
+    assert got[4, 0] == -128 * 255 * K and got[12, 0] == 127 * 255 * K and got[0, 0] == 0
+
+
+def test_saturation_and_rounding_pins_on_device():
+    # acc = 1 * x with w_scale 0.5: y = x / 2 hits every .5 tie; out_scale 1
+    K, M = 4, 256
+    W = np.zeros((4, K), np.int8)
+    W[0, 0] = 1
+    W[1, 0] = -1
+    W[2, 0] = 3
+    X = np.zeros((K, M), np.uint8)
+    X[0] = np.arange(256)
+    d = dict(w_scale=np.full(4, 0.5, np.float32), bias=None, x_scale=1.0, x_zero_point=0,
+             mid_scale=1.0, out_scale=1.0, out_zero_point=0)
+    for ot in ("s8", "u8"):
+        case = wl.Case("pins", 4, K, M, 0.0, wl.N4K1, ot, "none", with_bias=False)
+        got, ok = gpu_spmm(W, X, d, case)
+        assert ok
+        assert_parity(got, oracle_spmm(W, X, d, case), case)
+    got, _ = gpu_spmm(W, X, d, wl.Case("pins", 4, K, M, 0.0, wl.N4K1, "s8", "none", with_bias=False))
+    assert got[0, 1] == 0 and got[0, 3] == 2 and got[0, 5] == 2 and got[0, 7] == 4      # ties to even
+    assert got[1, 3] == -2 and got[1, 5] == -2 and got[2, 255] == 127 and got[1, 255] == -128
+
+
+def test_non_default_stream_and_repeated_runs():
+    case = wl.mini_cases()[1]
+    d = wl.make(case)
+    ref = oracle_spmm(d["W"], d["X"], d, case)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        for _ in range(3):
+            got, ok = gpu_spmm(d["W"], d["X"], d, case, stream=s)
+            assert ok
+            assert_parity(got, ref, case)
+
+
+def test_run_argument_errors_leave_output_untouched():
+    W = wl.sparse_weight(32, 64, 0.5, keys=(65,))
+    h = sp.spmm_pack(W)
+    try:
+        X = torch.zeros(64 * 16, dtype=torch.uint8, device="cuda")
+        out = torch.full((32 * 16,), 77, dtype=torch.int32, device="cuda")
+        ws = torch.ones(32, dtype=torch.float32, device="cuda")
+        ok_ep = sp.make_epilogue(ws, 1.0, 0, None, "none", "s32")
+        E = sp.SPMM_E_ARG
+        assert sp.spmm_run_status(h, None, 16, 16, ok_ep, out, 16) == E
+        assert sp.spmm_run_status(h, X, 16, 16, None, out, 16) == E
+        assert sp.spmm_run_status(h, X, 16, 16, ok_ep, None, 16) == E
+        assert sp.spmm_run_status(h, X, 0, 16, ok_ep, out, 16) == E
+        assert sp.spmm_run_status(h, X, 16, 15, ok_ep, out, 16) == E
+        assert sp.spmm_run_status(h, X, 16, 16, ok_ep, out, 15) == E
+        assert sp.spmm_run_status(None, X, 16, 16, ok_ep, out, 16) == E
+        bad = sp.make_epilogue(ws, 1.0, 0, None, "none", "s32"); bad.out_type = 9
+        assert sp.spmm_run_status(h, X, 16, 16, bad, out, 16) == E
+        bad = sp.make_epilogue(ws, 1.0, 0, None, "none", "s32"); bad.postop = 5
+        assert sp.spmm_run_status(h, X, 16, 16, bad, out, 16) == E
+        assert sp.spmm_run_status(h, X, 16, 16, sp.make_epilogue(None, 1.0, 0, None, "none", "f32"), out, 16) == E
+        assert sp.spmm_run_status(h, X, 16, 16, sp.make_epilogue(ws, 1.0, 0, None, "gelu", "s8", 1.0, 0, 1.0, None), out, 16) == E
+        assert sp.spmm_run_status(h, X, 16, 16, sp.make_epilogue(ws, 1.0, 0, None, "none", "s8", 0.0), out, 16) == E
+        assert sp.spmm_run_status(h, X, 16, 16, sp.make_epilogue(ws, 1.0, 0, None, "none", "s8", 1.0, 200), out, 16) == E
+        assert sp.spmm_run_status(h, X, 16, 16, sp.make_epilogue(ws, 1.0, 300, None, "none", "s32"), out, 16) == E
+        torch.cuda.synchronize()
+        assert (out == 77).all()
+        assert sp.spmm_run_status(h, X, 16, 16, ok_ep, out, 16) == sp.SPMM_OK
+        torch.cuda.synchronize()
+        assert (out == 0).all()
+    finally:
+        sp.spmm_destroy(h)
+
+
+def test_info_reports_device_bytes_and_plan():
+    W = wl.make(wl.large_cases()[0])["W"]
+    h = sp.spmm_pack(W)
+    try:
+        N, K, nnzb, padded, dev_bytes = sp.spmm_info(h)
+        steps = sp.spmm_layout_dims(h)[5]
+        assert dev_bytes >= steps * (1024 + 128) and padded == steps * 256
+        tm, rows, wgs = sp.spmm_plan(h, 6144, "s8")
+        assert tm > 0 and rows % 16 == 0 and wgs * tm * rows >= 6144 * N
+    finally:
+        sp.spmm_destroy(h)

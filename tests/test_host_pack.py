@@ -1,0 +1,170 @@
+"""Host logic of the library (no GPU): the C ABI loads and exports what the header
+declares, pack/unpack round-trips, block counts match the generator, and the compressed
+device layout -- decoded here in numpy exactly as the kernel's lanes read it -- reproduces
+the oracle's accumulator."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2306_16601_amd as sp
+import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "spmm.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(spmm_[a-z_0-9]+)\s*\(", hdr))
+    assert {"spmm_pack", "spmm_unpack", "spmm_info", "spmm_run", "spmm_make_gelu_lut",
+            "spmm_destroy", "spmm_status_string"} <= declared
+    L = ctypes.CDLL(sp.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(sp.EXPORTS)
+
+
+def test_status_strings():
+    assert sp.spmm_status_string(0) == "ok"
+    assert len({sp.spmm_status_string(i) for i in range(5)}) == 5
+
+
+def decode_layout_acc(handle, X):
+    """Replay the device layout on the CPU: per step, 64 list slots, 16 rows; activations
+    as (x - 128) with 128 * rowsum added back, exactly what the kernel accumulates."""
+    N, K, _, _, _ = sp.spmm_info(handle)
+    tile_rows, step_k, kc, n_tiles, n_seg, n_steps = sp.spmm_layout_dims(handle)
+    vals, idx, seg_ptr, rowsum = sp.spmm_layout_export(handle)
+    assert (tile_rows, step_k) == (16, 64)
+    M = X.shape[1]
+    Xs = X.astype(np.int64) - 128
+    acc = np.zeros((n_tiles * 16, M), dtype=np.int64)
+    for tile in range(n_tiles):
+        for seg in range(n_seg):
+            for s in range(seg_ptr[tile * n_seg + seg], seg_ptr[tile * n_seg + seg + 1]):
+                for g in range(4):
+                    for t in range(16):
+                        e = int(idx[s, 8 * g + (t % 8)])
+                        kl = (e & 0xFFFF) if t < 8 else (e >> 16)
+                        k = seg * kc + kl
+                        w = vals[s, 16 * g:16 * g + 16, t].view(np.int8).astype(np.int64)   # 16 rows
+                        if not w.any():
+                            assert kl < kc
+                            continue
+                        assert k < K
+                        acc[tile * 16:tile * 16 + 16] += w[:, None] * Xs[k][None, :]
+    acc += 128 * rowsum.astype(np.int64)[:, None]
+    return acc[:N]
+
+
+CASES = [
+    ("n4k1", 256, 256, 0.9), ("n1k4", 256, 256, 0.9), ("n4k1", 64, 1100, 0.8), ("n4k1", 50, 70, 0.5),
+    ("n1k4", 37, 131, 0.7), ("n4k1", 16, 2100, 0.95), ("n4k1", 3, 5, 0.0),
+]
+
+
+@pytest.mark.parametrize("orient,N,K,s", CASES)
+def test_roundtrip_counts_and_layout(orient, N, K, s):
+    W = wl.sparse_weight(N, K, s, orient, keys=(77, N, K))
+    h = sp.spmm_pack_host(W, orient)
+    try:
+        n, k, nnzb, padded, dev_bytes = sp.spmm_info(h)
+        assert (n, k) == (N, K) and dev_bytes == 0
+        assert np.array_equal(sp.spmm_unpack(h), W)
+        assert nnzb == wl.realised_block_sparsity(W, orient)[0]          # sparsity preserved
+        assert padded >= nnzb
+        X = wl.activations(K, 24, keys=(77, N, K))
+        ref = oracle.acc_s32(W, X).astype(np.int64)
+        assert np.array_equal(decode_layout_acc(h, X), ref)
+    finally:
+        sp.spmm_destroy(h)
+
+
+def test_layout_structure_tiny():
+    W = wl.make(wl.tiny_cases()[0])["W"]
+    h = sp.spmm_pack_host(W)
+    try:
+        tile_rows, step_k, kc, n_tiles, n_seg, n_steps = sp.spmm_layout_dims(h)
+        assert (n_tiles, n_seg) == (16, 1)
+        vals, idx, seg_ptr, rowsum = sp.spmm_layout_export(h)
+        assert seg_ptr[0] == 0 and seg_ptr[-1] == n_steps and np.all(np.diff(seg_ptr) >= 0)
+        assert np.array_equal(rowsum, W.astype(np.int32).sum(axis=1))
+        # the k list of tile 0 is the ascending union of its four block-rows, zero padded
+        union = np.flatnonzero((W[:16] != 0).any(axis=0))
+        got = []
+        for s in range(seg_ptr[0], seg_ptr[1]):
+            for g in range(4):
+                lo = [int(idx[s, 8 * g + t]) & 0xFFFF for t in range(8)]
+                hi = [int(idx[s, 8 * g + t]) >> 16 for t in range(8)]
+                got += lo + hi
+        assert got[:len(union)] == union.tolist()
+        assert all(v == 0 for v in got[len(union):])
+        assert len(got) == 64 * int(np.ceil(len(union) / 64))
+    finally:
+        sp.spmm_destroy(h)
+
+
+def test_unstructured_and_extreme_weights_pack_losslessly():
+    rng = np.random.default_rng(5)
+    W = rng.integers(-128, 128, size=(21, 45), dtype=np.int8)
+    W[rng.random(W.shape) < 0.6] = 0
+    for orient in ("n4k1", "n1k4"):
+        h = sp.spmm_pack_host(W, orient)
+        assert np.array_equal(sp.spmm_unpack(h), W)
+        X = wl.activations(45, 7, keys=(78,))
+        assert np.array_equal(decode_layout_acc(h, X), oracle.acc_s32(W, X).astype(np.int64))
+        sp.spmm_destroy(h)
+    Z = np.zeros((8, 8), np.int8)
+    h = sp.spmm_pack_host(Z)
+    assert sp.spmm_info(h)[2] == 0 and sp.spmm_layout_dims(h)[5] == 0
+    assert np.array_equal(sp.spmm_unpack(h), Z)
+    sp.spmm_destroy(h)
+
+
+def test_strided_weight_input():
+    big = wl.sparse_weight(32, 64, 0.75, keys=(79,))
+    W = big[:, :40]                                  # ldw = 64 > K = 40
+    h = sp.spmm_pack_host(W)
+    assert np.array_equal(sp.spmm_unpack(h), W)
+    sp.spmm_destroy(h)
+
+
+def test_pack_argument_errors():
+    L = sp.lib()
+    W = np.zeros((4, 4), np.int8)
+    h = ctypes.c_void_p()
+    p = W.ctypes.data_as(ctypes.c_void_p)
+    assert L.spmm_pack_host(None, 4, 4, 4, 0, ctypes.byref(h)) == sp.SPMM_E_ARG
+    assert L.spmm_pack_host(p, 4, 4, 4, 0, None) == sp.SPMM_E_ARG
+    assert L.spmm_pack_host(p, 0, 4, 4, 0, ctypes.byref(h)) == sp.SPMM_E_ARG
+    assert L.spmm_pack_host(p, 4, -1, 4, 0, ctypes.byref(h)) == sp.SPMM_E_ARG
+    assert L.spmm_pack_host(p, 4, 4, 3, 0, ctypes.byref(h)) == sp.SPMM_E_ARG
+    assert L.spmm_pack_host(p, 4, 4, 4, 7, ctypes.byref(h)) == sp.SPMM_E_ARG
+    assert L.spmm_pack_host(p, 4, 70000, 70000, 0, ctypes.byref(h)) == sp.SPMM_E_UNSUPPORTED
+    assert h.value is None
+    assert L.spmm_unpack(None, p, 4) == sp.SPMM_E_ARG
+    assert L.spmm_info(None, None, None, None, None, None) == sp.SPMM_E_ARG
+    L.spmm_destroy(None)                             # allowed
+    hh = sp.spmm_pack_host(W)
+    assert L.spmm_unpack(hh, p, 3) == sp.SPMM_E_ARG
+    ep = sp.make_epilogue()
+    assert sp.spmm_run_status(hh, 16, 4, 4, ep, 16, 4) == sp.SPMM_E_ARG      # host-only handle
+    assert L.spmm_set_tuning(hh, 48, 0) == sp.SPMM_E_UNSUPPORTED
+    assert L.spmm_set_tuning(hh, 64, 2) == sp.SPMM_OK
+    sp.spmm_destroy(hh)
+
+
+def test_gelu_lut_matches_oracle_table_entry_by_entry():
+    for mid, outs, zp, ot in [(0.1, 0.1, 0, "s8"), (0.42, 0.42, 0, "s8"), (0.05, 0.02, -100, "s8"),
+                              (0.3, 0.15, 4, "u8")]:
+        assert np.array_equal(sp.spmm_make_gelu_lut(mid, outs, zp, ot), oracle.gelu_lut(mid, outs, zp, ot))
+    L = sp.lib()
+    buf = np.zeros(256, np.int8).ctypes.data_as(ctypes.c_void_p)
+    assert L.spmm_make_gelu_lut(0.0, 1.0, 0, sp.SPMM_OUT_S8, buf) == sp.SPMM_E_ARG
+    assert L.spmm_make_gelu_lut(1.0, 1.0, 0, sp.SPMM_OUT_F32, buf) == sp.SPMM_E_ARG
+    assert L.spmm_make_gelu_lut(1.0, 1.0, 300, sp.SPMM_OUT_S8, buf) == sp.SPMM_E_ARG
+    assert L.spmm_make_gelu_lut(1.0, 1.0, 0, sp.SPMM_OUT_S8, None) == sp.SPMM_E_ARG
