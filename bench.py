@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the 4x1 structured-sparse INT8 SpMM on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|base|mini]
+
+One "step" is one pass of the whole hot path (pack is done once, outside) over the
+workload's SpMM calls: for the default `large` workload the BERT-Large layer shapes
+(1024x1024, 4096x1024, 1024x4096) at 90 % and 80 % 4x1-block sparsity with
+M = 16 x 384 = 6144 tokens, fused bias + GELU + int8 requantisation (table path).
+Inputs are seeded synthetic tensors already resident in HBM; each call rotates through
+several distinct activation/output buffers so that repeated launches do not hit in the
+last-level cache.  Prints ONE JSON line.
+
+metric  : dense-equivalent TOPS = sum(2*N*K*M) / time (the dense GEMM work the sparse
+          kernel replaces); non-zero TOPS (2 * 4 * nnz_blocks * M, padding excluded) and
+          the fraction of the binding roofline are reported beside it.
+roofline: algorithmic bytes per launch = K*M (X once) + N*M*sizeof(out) + 6 B per non-zero
+          4x1 block (4 int8 values + 2-byte index) + 4*(N/4+1) (block-row pointers)
+          + 12*N (scale, bias, row sum), divided by the average launch duration measured
+          here with HIP events, against 8 TB/s; t_int8 = non-zero ops / 5 POP/s never binds
+          for these shapes and is printed per shape for reference.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+INT8_MFMA_PEAK_TOPS = 5000.0
+ROTATE = 3   # distinct X/out buffer sets per SpMM (6 calls x 3 sets x ~30 MB > 256 MB of cache)
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/), or None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_bytes(N, K, M, nnz_blocks, out_elem):
+    return K * M + N * M * out_elem + 6 * nnz_blocks + 4 * (N // 4 + 1) + 12 * N
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="large", choices=["large", "base", "mini"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--tuning", default="", help="token_tile,row_tiles_per_wave override (0 = automatic)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the SpMM shards trivially over tokens or output "
+              "channels, see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2306_16601_amd as sp
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    sp.lib()   # fail loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    if args.workload == "large":
+        cases = wl.large_cases()
+        wname = "bert_large_layers_m6144_s90_s80_gelu_s8"
+    elif args.workload == "base":
+        cases = [c for c in wl.base_cases(batches=(32,), sparsities=(0.9, 0.8))]
+        wname = "bert_base_layers_m4096_s90_s80_f32"
+    else:
+        cases = wl.mini_cases()
+        wname = "bert_mini_ffn_pair_m1024_s80"
+    out_elem = {"s32": 4, "f32": 4, "s8": 1, "u8": 1}
+    tdt = {"s32": torch.int32, "f32": torch.float32, "s8": torch.int8, "u8": torch.uint8}
+
+    # ------------------------------------------------------------------ set up (not timed)
+    calls = []
+    for case in cases:
+        d = wl.make(case)
+        h = sp.spmm_pack(d["W"], case.orientation)
+        if args.tuning:
+            tm, r = (int(v) for v in args.tuning.split(","))
+            sp.spmm_set_tuning(h, tm, r)
+        N, K, nnzb, padded, dev_bytes = sp.spmm_info(h)
+        ws = torch.from_numpy(d["w_scale"]).cuda()
+        bias = torch.from_numpy(d["bias"]).cuda() if d["bias"] is not None else None
+        lut = None
+        if case.postop == "gelu" and case.out_type in ("s8", "u8"):
+            lut = torch.from_numpy(sp.spmm_make_gelu_lut(d["mid_scale"], d["out_scale"], 0, case.out_type)).cuda()
+        ep = sp.make_epilogue(ws, d["x_scale"], 0, bias, case.postop, case.out_type, d["out_scale"], 0,
+                              d["mid_scale"], lut)
+        Xs = [torch.from_numpy(d["X"]).cuda() for _ in range(ROTATE)]
+        outs = [torch.empty((N, case.M), dtype=tdt[case.out_type], device="cuda") for _ in range(ROTATE)]
+        calls.append(dict(case=case, d=d, h=h, ep=ep, keep=(ws, bias, lut), Xs=Xs, outs=outs, N=N, K=K,
+                          M=case.M, nnzb=nnzb, padded=padded, dev_bytes=dev_bytes,
+                          bytes=algorithmic_bytes(N, K, case.M, nnzb, out_elem[case.out_type]),
+                          dense_ops=2.0 * N * K * case.M, nnz_ops=2.0 * 4 * nnzb * case.M,
+                          plan=sp.spmm_plan(h, case.M, case.out_type)))
+
+    def launch(c, it):
+        j = it % ROTATE
+        sp.spmm_run(c["h"], c["Xs"][j], c["M"], c["M"], c["ep"], c["outs"][j], c["M"], stream.cuda_stream)
+
+    # ------------------------------------------------------------------ warm-up, then timed region
+    for it in range(args.warmup):
+        for c in calls:
+            launch(c, it)
+    torch.cuda.synchronize()
+
+    nc = len(calls)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(nc + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for it in range(args.steps):
+        ev[it][0].record(stream)
+        for ci, c in enumerate(calls):
+            launch(c, it)
+            ev[it][ci + 1].record(stream)
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+    step_ms = [ev[it][0].elapsed_time(ev[it][nc]) for it in range(args.steps)]
+    # steps are back to back on one stream: total = first event of step 0 .. last event of the last step
+    total_ms = ev[0][0].elapsed_time(ev[args.steps - 1][nc])
+    ms_per_step = total_ms / args.steps
+    per_call_us = np.array([[ev[it][ci].elapsed_time(ev[it][ci + 1]) * 1e3 for ci in range(nc)]
+                            for it in range(args.steps)])
+    avg_us = per_call_us.mean(axis=0)
+    med_us = np.median(per_call_us, axis=0)
+    min_us = per_call_us.min(axis=0)
+
+    dense_ops = sum(c["dense_ops"] for c in calls)
+    nnz_ops = sum(c["nnz_ops"] for c in calls)
+    value = dense_ops / (ms_per_step * 1e-3) / 1e12
+    nnz_tops = nnz_ops / (ms_per_step * 1e-3) / 1e12
+
+    # ------------------------------------------------------------------ dense int8 GEMM of the same shapes (vendor BLAS)
+    dense = {}
+    if not args.no_dense:
+        for (N, K) in sorted({(c["N"], c["K"]) for c in calls}):
+            M = calls[0]["M"]
+            try:
+                a = torch.randint(-128, 127, (M, K), dtype=torch.int8, device="cuda")
+                b = torch.randint(-128, 127, (N, K), dtype=torch.int8, device="cuda").t()
+                for _ in range(5):
+                    torch._int_mm(a, b)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(20):
+                    torch._int_mm(a, b)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 20
+                dense["%dx%d" % (N, K)] = {"us": round(us, 2), "tops": round(2.0 * N * K * M / us / 1e6, 1)}
+            except Exception as exc:   # the comparator is context only
+                dense["%dx%d" % (N, K)] = {"error": repr(exc)[:120]}
+
+    # ------------------------------------------------------------------ per-shape rows + roofline of the SpMM kernel
+    rows = []
+    for ci, c in enumerate(calls):
+        t_hbm = c["bytes"] / (HBM_PEAK_GBS * 1e9) * 1e6
+        t_int8 = c["nnz_ops"] / (INT8_MFMA_PEAK_TOPS * 1e12) * 1e6
+        t = float(avg_us[ci])
+        key = "%dx%d" % (c["N"], c["K"])
+        rows.append({
+            "case": c["case"].name, "us_avg": round(t, 2), "us_median": round(float(med_us[ci]), 2),
+            "us_min": round(float(min_us[ci]), 2),
+            "dense_equiv_tops": round(c["dense_ops"] / t / 1e6, 1), "nonzero_tops": round(c["nnz_ops"] / t / 1e6, 1),
+            "algorithmic_bytes": int(c["bytes"]), "t_hbm_us": round(t_hbm, 2), "t_int8_us": round(t_int8, 2),
+            "bound": "hbm" if t_hbm >= t_int8 else "mfma", "roofline_frac": round(max(t_hbm, t_int8) / t, 4),
+            "nnz_blocks": int(c["nnzb"]), "padded_blocks": int(c["padded"]),
+            "plan": {"token_tile": c["plan"][0], "rows_per_wg": c["plan"][1], "workgroups": c["plan"][2]},
+            "speedup_vs_dense_gemm": (round(dense[key]["us"] / t, 2) if key in dense and "us" in dense[key] else None),
+            "sha256": {"W": wl.sha256(c["d"]["W"])[:16], "X": wl.sha256(c["d"]["X"])[:16]},
+        })
+    tot_bytes = sum(c["bytes"] for c in calls)
+    tot_us = float(avg_us.sum())
+    achieved = tot_bytes / (tot_us * 1e-6) / 1e9
+    roofline = {
+        "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
+        "kernel": sp.spmm_kernel_name(), "launches_per_step": nc,
+        "avg_launch_us": round(tot_us / nc, 3), "algorithmic_bytes_per_launch": int(tot_bytes / nc),
+    }
+
+    # ------------------------------------------------------------------ CPU baseline: the oracle on the host cores
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = [c for c in calls if abs(c["case"].sparsity - calls[0]["case"].sparsity) < 1e-9]
+        ops, secs, parity = 0.0, 0.0, True
+        for c in sample:
+            d, case = c["d"], c["case"]
+            launch(c, 0)
+            torch.cuda.synchronize()
+            got = c["outs"][0].cpu().numpy()
+            t1 = time.perf_counter()
+            ref = oracle.spmm(d["W"], d["X"], d["w_scale"], d["x_scale"], d["bias"], case.postop, case.out_type,
+                              d["out_scale"], 0, d["mid_scale"])
+            secs += time.perf_counter() - t1
+            ops += c["dense_ops"]
+            if case.out_type == "f32" and case.postop == "gelu":
+                parity &= bool(np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-7))
+            else:
+                parity &= bool(np.array_equal(got, ref))
+        cpu = {"value": round(ops / secs / 1e12, 5), "unit": "TOPS (dense-equivalent)", "cores": oracle.num_threads(),
+               "kind": "oracle", "seconds": round(secs, 2),
+               "sample": "%d SpMM calls of the workload (%s), one run each" % (
+                   len(sample), ", ".join(c["case"].name for c in sample)),
+               "gpu_matches_oracle": parity}
+
+    for c in calls:
+        sp.spmm_destroy(c["h"])
+
+    line = {
+        "metric": "SpMM dense-equivalent TOPS (4x1 block-sparse INT8, BERT shapes, fused epilogue)",
+        "value": round(value, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": wname, "calls_per_step": nc, "tokens": calls[0]["M"], "orientation": "n4k1",
+                   "buffer_rotation": ROTATE},
+        "nonzero_tops": round(nnz_tops, 2),
+        "roofline": roofline, "cpu_baseline": cpu, "dense_int8_gemm": dense, "per_call": rows,
+        "step_ms_median": round(float(np.median(step_ms)), 5), "host_wall_s": round(wall_s, 4),
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -15,7 +15,8 @@ struct spmm_handle {
     spmm::HostLayout hl;           // host copy of the row-tile union layout
     // device copy of the same
     bool on_device = false;
-    int kc = 0, nseg = 0, ntiles = 0, max_steps_per_tile = 0;
+    int kc = 0, nseg = 0, ntiles = 0, max_steps_per_tile = 0, max_steps_per_segment = 0;
+    int num_cus = 256;
     int64_t nsteps = 0;
     uint8_t* d_vals = nullptr;
     uint32_t* d_idx = nullptr;
@@ -30,10 +31,13 @@ namespace {
 template <typename T>
 hipError_t upload(T*& dst, const std::vector<T>& src, int64_t& total)
 {
-    const size_t bytes = std::max<size_t>(src.size() * sizeof(T), 16);
+    // at least one zero step's worth, so that step index 0 is always readable
+    const size_t bytes = std::max<size_t>(src.size() * sizeof(T), spmm::STEP_VAL_BYTES);
     hipError_t e = hipMalloc((void**)&dst, bytes);
     if (e != hipSuccess) return e;
     total += (int64_t)bytes;
+    if (src.size() * sizeof(T) < bytes) e = hipMemset(dst, 0, bytes);
+    if (e != hipSuccess) return e;
     if (!src.empty()) e = hipMemcpy(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
     return e;
 }
@@ -74,9 +78,15 @@ static spmm_status_t pack_common(const int8_t* W_host, int64_t N, int64_t K, int
     const spmm::HostLayout& hl = h->hl;
     h->kc = hl.kc; h->nseg = hl.nseg; h->ntiles = hl.ntiles; h->nsteps = hl.nsteps;
     h->max_steps_per_tile = hl.max_steps_per_tile;
+    h->max_steps_per_segment = hl.max_steps_per_segment;
 
     if (to_device) {
         hipError_t e = hipGetDevice(&h->device);
+        if (e == hipSuccess) {
+            int cus = 0;
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device) == hipSuccess && cus > 0)
+                h->num_cus = cus;
+        }
         if (e == hipSuccess) e = upload(h->d_vals, hl.vals, h->device_bytes);
         if (e == hipSuccess) e = upload(h->d_idx, hl.idx, h->device_bytes);
         if (e == hipSuccess) e = upload(h->d_seg_ptr, hl.seg_ptr, h->device_bytes);
@@ -153,9 +163,10 @@ spmm_status_t spmm_plan(const spmm_handle_t* h, int64_t M, spmm_out_t out_type, 
                         int32_t* rows_per_workgroup, int64_t* workgroups)
 {
     if (!h || M <= 0) return SPMM_E_ARG;
-    const spmm::Plan p = spmm::make_plan(h->bsr.N, h->bsr.K, M, h->ntiles, out_type, h->force_tm, h->force_r);
+    const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r);
     if (token_tile) *token_tile = p.token_tile;
     if (rows_per_workgroup) *rows_per_workgroup = p.waves * p.row_tiles_per_wave * spmm::TILE_ROWS;
+    (void)out_type;
     if (workgroups) *workgroups = p.workgroups;
     return SPMM_OK;
 }
@@ -163,7 +174,7 @@ spmm_status_t spmm_plan(const spmm_handle_t* h, int64_t M, spmm_out_t out_type, 
 spmm_status_t spmm_set_tuning(spmm_handle_t* h, int32_t token_tile, int32_t row_tiles_per_wave)
 {
     if (!h || token_tile < 0 || row_tiles_per_wave < 0) return SPMM_E_ARG;
-    const int tm = token_tile ? token_tile : 64;
+    const int tm = token_tile ? token_tile : 128;
     const int r = row_tiles_per_wave ? row_tiles_per_wave : 1;
     if (!spmm::plan_supported(tm, r)) return SPMM_E_UNSUPPORTED;
     h->force_tm = token_tile;
@@ -215,7 +226,7 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
     const size_t vec = quant ? 4 : 16;     // 4 tokens per store
     a.out_vec_ok = aligned(out_dev, vec) && ((ldo * esz) % (int64_t)vec == 0);
 
-    const spmm::Plan p = spmm::make_plan(h->bsr.N, h->bsr.K, M, h->ntiles, ot, h->force_tm, h->force_r);
+    const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r);
     const int rc = spmm::launch_spmm(p, a, ot, gelu ? SPMM_POST_GELU : SPMM_POST_NONE, hip_stream);
     return rc == 0 ? SPMM_OK : SPMM_E_DEVICE;
 }

@@ -121,6 +121,7 @@ void layout_from_bsr(const Bsr& b, int kc, HostLayout& out)
     out.seg_ptr.assign(1, 0);
     out.rowsum.assign((size_t)out.ntiles * TILE_ROWS, 0);
     out.max_steps_per_tile = 0;
+    out.max_steps_per_segment = 0;
 
     std::vector<int8_t> buf((size_t)TILE_ROWS * K);
     std::vector<int32_t> list;
@@ -164,6 +165,7 @@ void layout_from_bsr(const Bsr& b, int kc, HostLayout& out)
                     }
             }
             steps_this_tile += nsteps;
+            out.max_steps_per_segment = std::max(out.max_steps_per_segment, nsteps);
             out.seg_ptr.push_back(out.seg_ptr.back() + nsteps);
         }
         out.max_steps_per_tile = std::max(out.max_steps_per_tile, steps_this_tile);

@@ -30,12 +30,13 @@ constexpr int TILE_ROWS = 16;
 constexpr int STEP_K = 64;
 constexpr int STEP_VAL_BYTES = TILE_ROWS * STEP_K;   // 1024
 constexpr int STEP_IDX_DWORDS = STEP_K / 2;          // 32
-constexpr int SEGMENT_ROWS = 1024;                   // kc: activation rows resident in LDS at once
+constexpr int SEGMENT_ROWS = 512;                    // kc: activation rows of one K segment (one LDS buffer)
 
 struct HostLayout {
     int kc = 0, nseg = 0, ntiles = 0;
     int64_t nsteps = 0;
     int max_steps_per_tile = 0;
+    int max_steps_per_segment = 0;  // largest step count of any (tile, segment)
     std::vector<uint8_t> vals;      // nsteps * 1024
     std::vector<uint32_t> idx;      // nsteps * 32
     std::vector<int32_t> seg_ptr;   // ntiles * nseg + 1
@@ -73,6 +74,8 @@ struct KernelArgs {
     int N, K, M;
     int kc, nseg, ntiles;
     int n_tok_tiles, n_row_groups;
+    int n_streams;       // persistent kernel: workgroups per row group, each walking token tiles j*n_streams + stream
+    int xcd_map;         // 1: workgroup ids are decoded so that a token-tile stream stays on one XCD
     int corr_mul;        // 128 - x_zero_point: the activations are multiplied as (x - 128)
     float x_scale, inv_out, inv_mid, out_zp_f;
     int x_vec_ok;        // X base 16-byte aligned and ldx % 16 == 0
@@ -80,14 +83,16 @@ struct KernelArgs {
 };
 
 struct Plan {
-    int token_tile;      // TM
-    int row_tiles_per_wave;  // R
-    int waves;           // NW
+    int token_tile;          // TM: 128 = pipelined persistent kernel, 64 = simple kernel
+    int row_tiles_per_wave;  // R (simple kernel only)
+    int waves;               // NW
+    int max_steps;           // unroll bound of the per-segment step loop (pipelined kernel)
+    int n_row_groups, n_tok_tiles, n_streams, xcd_map;
     int64_t workgroups;
 };
 
 bool plan_supported(int token_tile, int row_tiles_per_wave);
-Plan make_plan(int64_t N, int64_t K, int64_t M, int ntiles, spmm_out_t out_type, int force_tm, int force_r);
+Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int force_r);
 // Launches the SpMM kernel; returns a hipError_t value as int (0 = success).
 int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_postop_t postop, void* stream);
 

@@ -16,12 +16,21 @@
 //  * u8 x s8: the matrix instruction multiplies signed bytes, so activations are stored in
 //    LDS as x - 128 (one xor per dword while staging) and 128 * rowsum(W) is added back
 //    by initialising the accumulators with it; exact in int32.
-//  * post-operators (Section 3.3) are applied to the accumulators in registers.
+//  * post-operators (Section 3.3) are applied to the accumulators in registers; the
+//    GELU->int8 chain is the 256-entry table of Algorithm 2, held in LDS.
+//  * the two-dimensional blocking over output rows and tokens of Section 3.2 becomes the
+//    workgroup decomposition: a workgroup owns a group of row tiles and walks over token
+//    tiles, so the compressed weights it needs stay in registers.
 //
 // Lane roles of the matrix instruction (D = A.B, 64 lanes, g = lane / 16, c = lane % 16):
 //   A operand (activations): row = token c, bytes t = k-list slots 16g .. 16g+15
 //   B operand (weights)    : column = output row c, same k slots
 //   D                      : D[token 4g + r][output row c], r = 0..3
+//
+// ds_read_b64_tr_b8 within a 16-lane group: the lane at position p supplies the address of
+// 8 bytes; result lane p receives, as byte t, byte (p % 8) of the 8 bytes addressed by
+// source position 2t + p / 8.  With source position 2t + h pointing at tokens 8h .. 8h+7
+// of activation row k_t, result lane p holds token p of rows k_0 .. k_7.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -35,12 +44,7 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v2i* lds_v2i_ptr;
 
-template <int TM>
-struct TileCfg {
-    static constexpr int STRIDE = TM + 16;   // LDS row pitch in bytes: rows k, k+1, .. start 4 banks apart
-    static constexpr int LDS_BYTES = SEGMENT_ROWS * STRIDE;
-    static constexpr int PIECES = TM / 16;   // 16-byte pieces per activation row
-};
+constexpr int FLIP = (int)0x80808080;   // x ^ 0x80 == x - 128 as a signed byte
 
 // Exact GELU evaluated in double on the binary32 pre-activation, rounded once to binary32.
 __device__ __forceinline__ float gelu_f32(float y)
@@ -49,11 +53,12 @@ __device__ __forceinline__ float gelu_f32(float y)
     return (float)(0.5 * x * erfc(-x * 0.70710678118654752440));
 }
 
-template <int OUT, int POST>
+// Post-operators for 4 consecutive tokens m0..m0+3 of output row n.  `lut` is the table of
+// Algorithm 2 (any address space; LDS in the pipelined kernel).
+template <int OUT, int POST, typename LutPtr>
 __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, const float s, const float b,
-                                        const int n, const int m0)
+                                        const int n, const int m0, LutPtr lut)
 {
-    // acc: 4 consecutive tokens m0..m0+3 of output row n.
     const int valid = a.M - m0;   // > 0 guaranteed by caller
     if constexpr (OUT == SPMM_OUT_S32) {
         int32_t* o = (int32_t*)a.out + (int64_t)n * a.ldo + m0;
@@ -86,9 +91,10 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     // key = sat_s8(rint(y / mid_scale)); looked up as key + 128 in [0, 255]
+                    // (v_cvt_pk_u8_f32 converts with saturation to [0, 255])
                     const float t = rintf(y[r] * a.inv_mid) + 128.0f;
                     const uint32_t key = __builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u);
-                    q[r] = (uint32_t)(uint8_t)a.lut[key];
+                    q[r] = (uint32_t)(uint8_t)lut[key];
                 }
             } else {
                 const float lo = (OUT == SPMM_OUT_U8) ? 0.0f : -128.0f;
@@ -110,17 +116,280 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
     }
 }
 
-// One workgroup = NW waves; wave w owns R row tiles; the workgroup covers NW*R*16 output rows
-// and TM tokens, and walks over the K segments with the activations of one segment in LDS.
-template <int TM, int NW, int R, int OUT, int POST>
+// s_waitcnt vmcnt(0) only (expcnt / lgkmcnt fields left at their maxima).  Issued at the end
+// of a phase, when the prefetches started at its beginning have long landed: it tells the
+// compiler's wait-count bookkeeping that no global load is outstanding, so the next phase's
+// multiply loop does not stall on the prefetches issued just before it.
+__device__ __forceinline__ void wait_global_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// 16 bytes of activation row `krow` starting at token `col`; tokens >= M read as 0.
+__device__ __forceinline__ v4i load_x16(const KernelArgs& a, const int krow, const int col)
+{
+    const uint8_t* src = a.X + (int64_t)krow * a.ldx + col;
+    if (a.x_vec_ok && col + 16 <= a.M) return *(const v4i*)src;
+    v4i v = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (col + j < a.M) v[j >> 2] |= (int)((uint32_t)src[j] << (8 * (j & 3)));
+    return v;
+}
+
+// =======================================================================================
+// Pipelined persistent kernel (the one spmm_run launches by default).
+//
+// Workgroup = NW waves (16 or 8), one workgroup per CU.  Wave w owns row tile NW*rg + w (16 output rows) for the
+// whole kernel; the workgroup walks over token tiles of 128 tokens (stream, stream + S, ..)
+// and, inside a token tile, over the K segments of 512 rows.  One (token tile, segment)
+// pair is a "phase".  LDS holds two activation buffers [512 rows][128 + 16 bytes]; while
+// phase p multiplies out of buffer p % 2, the global loads for phase p+1 are in flight in
+// registers and are written to the other buffer afterwards; one barrier per phase.
+// The compressed weights of a phase (at most MAXS steps of 64 listed k) live in one of two
+// register sets; with at most two segments they are loaded once per workgroup and reused
+// for every token tile, otherwise they are prefetched one phase ahead.
+// =======================================================================================
+constexpr int PIPE_TM = 128;
+constexpr int PIPE_STRIDE = PIPE_TM + 16;                   // 144 B: consecutive rows start 4 banks apart
+constexpr int PIPE_BUF_BYTES = SEGMENT_ROWS * PIPE_STRIDE;  // 73728 B
+constexpr int PIPE_PIECES = PIPE_TM / 16;                   // 8 MFMA token sub-tiles
+constexpr int PIPE_LDS = 2 * PIPE_BUF_BYTES + 256;
+
+// Post-operators + store for one full token tile of one wave, everything in bounds and
+// aligned: lane (g, c) holds tokens tok0 + 16 i + 4 g + {0..3} of output row n.
+template <int OUT, int POST>
+__device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i (&acc)[PIPE_PIECES], const float scale,
+                                                 const float bias, const int n, const int tok, const uint8_t* lut_lds)
+{
+    if constexpr (OUT == SPMM_OUT_S32) {
+        int32_t* o = (int32_t*)a.out + ((int64_t)n * a.ldo + tok);
+#pragma unroll
+        for (int i = 0; i < PIPE_PIECES; ++i) *(v4i*)(o + 16 * i) = acc[i];
+    } else if constexpr (OUT == SPMM_OUT_F32) {
+        float* o = (float*)a.out + ((int64_t)n * a.ldo + tok);
+#pragma unroll
+        for (int i = 0; i < PIPE_PIECES; ++i) {
+            v4f y;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                y[r] = __fmaf_rn((float)acc[i][r], scale, bias);
+                if constexpr (POST == SPMM_POST_GELU) y[r] = gelu_f32(y[r]);
+            }
+            *(v4f*)(o + 16 * i) = y;
+        }
+    } else {
+        uint8_t* o = (uint8_t*)a.out + ((int64_t)n * a.ldo + tok);
+#pragma unroll
+        for (int i = 0; i < PIPE_PIECES; ++i) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float y = __fmaf_rn((float)acc[i][r], scale, bias);
+                uint32_t q;
+                if constexpr (POST == SPMM_POST_GELU) {
+                    const float t = rintf(y * a.inv_mid) + 128.0f;
+                    q = lut_lds[__builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u)];
+                } else {
+                    const float lo = (OUT == SPMM_OUT_U8) ? 0.0f : -128.0f;
+                    const float hi = (OUT == SPMM_OUT_U8) ? 255.0f : 127.0f;
+                    q = (uint32_t)((int)fminf(hi, fmaxf(lo, rintf(y * a.inv_out) + a.out_zp_f))) & 0xffu;
+                }
+                word |= q << (8 * r);
+            }
+            *(uint32_t*)(o + 16 * i) = word;
+        }
+    }
+}
+
+template <int NW, int MAXS, int OUT, int POST>
 __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
 {
-    using C = TileCfg<TM>;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[C::LDS_BYTES];
+    constexpr int NTHREADS = NW * 64;
+    constexpr int XLOADS = SEGMENT_ROWS * PIPE_PIECES / NTHREADS;   // 16-byte loads per thread and phase
+    __shared__ __attribute__((aligned(16))) uint8_t lds[PIPE_LDS];
+    uint8_t* const lut_lds = lds + 2 * PIPE_BUF_BYTES;
 
-    // XCD-aware decomposition: workgroups are handed to the 8 XCDs round-robin, so the
-    // workgroups that share a token tile (and therefore its activations) get ids that are
-    // congruent mod 8 and meet in the same L2.
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+
+    // workgroup -> (row group, token-tile stream).  Workgroups go to the 8 XCDs round-robin;
+    // with xcd_map all row groups of one stream get ids congruent mod 8 and share an L2.
+    int rg, stream;
+    {
+        const int b = blockIdx.x;
+        if (a.xcd_map) {
+            const int local = b >> 3;
+            stream = (b & 7) + 8 * (local / a.n_row_groups);
+            rg = local % a.n_row_groups;
+        } else {
+            rg = b % a.n_row_groups;
+            stream = b / a.n_row_groups;
+        }
+    }
+    const int S = a.n_streams;
+    const int n_my = (a.n_tok_tiles - stream + S - 1) / S;   // token tiles of this stream (>= 1)
+    const int total = n_my * a.nseg;                          // phases
+
+    const int tile = rg * NW + wave;
+    const bool have_tile = tile < a.ntiles;
+    const int n = tile * TILE_ROWS + c;                       // this lane's output row
+    const int init = have_tile ? a.rowsum[n] * a.corr_mul : 0;
+    float scale = 0.0f, bias = 0.0f;
+    if constexpr (OUT != SPMM_OUT_S32) {
+        if (have_tile && n < a.N) {
+            scale = a.w_scale[n] * a.x_scale;
+            if (a.bias) bias = a.bias[n];
+        }
+    }
+    if constexpr (POST == SPMM_POST_GELU && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8)) {
+        if (tid < 256) lut_lds[tid] = (uint8_t)a.lut[tid];
+    }
+
+    v4i A0[MAXS], A1[MAXS];
+    uint32_t I0[MAXS], I1[MAXS];
+    int n0 = 0, n1 = 0;
+    v4i xr[XLOADS];
+    v4i acc[PIPE_PIECES];
+#pragma unroll
+    for (int i = 0; i < PIPE_PIECES; ++i) acc[i] = (v4i){init, init, init, init};
+
+    // per-thread staging coordinates: XLOADS rows (NTHREADS / 8 apart), one 16-byte piece
+    const int x_row0 = tid >> 3, x_piece = tid & 7;
+    const uint32_t x_lds0 = (uint32_t)x_row0 * PIPE_STRIDE + x_piece * 16;
+
+    // ---- global loads of the activations of phase q into registers.  The common case (16-byte
+    // aligned rows, full token tile) is branch-free so that all loads are in flight together;
+    // rows past the end of K are redirected to the last valid row (never multiplied).
+    auto x_issue = [&](const int q) {
+        const int j = q / a.nseg, seg = q - j * a.nseg;
+        const int tok0 = (stream + j * S) * PIPE_TM;
+        const int k0 = seg * SEGMENT_ROWS;
+        const int last = min(SEGMENT_ROWS, a.K - k0) - 1;
+        if (a.x_vec_ok && tok0 + PIPE_TM <= a.M) {
+            const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0 + x_piece * 16;
+#pragma unroll
+            for (int u = 0; u < XLOADS; ++u) {
+                const int row = min(x_row0 + u * (NTHREADS / 8), last);
+                xr[u] = *(const v4i*)(src + (int64_t)row * a.ldx);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < XLOADS; ++u) {
+                const int row = min(x_row0 + u * (NTHREADS / 8), last);
+                xr[u] = load_x16(a, k0 + row, tok0 + x_piece * 16);
+            }
+        }
+    };
+    // ---- ... and from registers into LDS buffer q % 2, as x - 128
+    auto x_commit = [&](const int q) {
+        uint8_t* buf = lds + (q & 1) * PIPE_BUF_BYTES + x_lds0;
+#pragma unroll
+        for (int u = 0; u < XLOADS; ++u)
+            *(v4i*)(buf + u * (NTHREADS / 8) * PIPE_STRIDE) = xr[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+    };
+    // ---- compressed weights + activation-row indices of (tile, segment of phase q).  Loads are
+    // unconditional (slots past the segment's step count re-read step 0 and are never used).
+    auto w_issue = [&](const int q, v4i (&A)[MAXS], uint32_t (&I)[MAXS], int& cnt) {
+        cnt = 0;
+        int s0 = 0;
+        if (have_tile) {
+            const int seg = q % a.nseg;
+            s0 = a.seg_ptr[tile * a.nseg + seg];
+            cnt = a.seg_ptr[tile * a.nseg + seg + 1] - s0;
+        }
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) {
+            const int step = (s < cnt) ? s0 + s : 0;
+            A[s] = *(const v4i*)(a.vals + (int64_t)step * STEP_VAL_BYTES + lane * 16);
+            I[s] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
+        }
+    };
+    // ---- multiply phase q: gather + transpose out of LDS, 8 matrix instructions per step
+    auto multiply = [&](const int q, const v4i (&A)[MAXS], const uint32_t (&I)[MAXS], const int cnt) {
+        const uint32_t base = (uint32_t)(q & 1) * PIPE_BUF_BYTES + (c & 1) * 8;
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) {
+            if (s < cnt) {
+                // this lane supplies the address of list slot 16g + c/2 (and + 8), token half c & 1
+                const uint32_t a0 = (I[s] & 0xffffu) * PIPE_STRIDE + base;
+                const uint32_t a1 = (I[s] >> 16) * PIPE_STRIDE + base;
+#pragma unroll
+                for (int i = 0; i < PIPE_PIECES; ++i) {
+                    const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0 + 16 * i));
+                    const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1 + 16 * i));
+                    const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
+                    acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, A[s], acc[i], 0, 0, 0);
+                }
+            }
+        }
+    };
+    // ---- after the last segment of a token tile: post-operators, store, reset accumulators
+    auto finish = [&](const int q) {
+        const int j = q / a.nseg;
+        if (q - j * a.nseg != a.nseg - 1) return;
+        const int tok0 = (stream + j * S) * PIPE_TM;
+        if (have_tile && n < a.N) {
+            if (a.out_vec_ok && tok0 + PIPE_TM <= a.M) {
+                finish_tile_fast<OUT, POST>(a, acc, scale, bias, n, tok0 + 4 * g, lut_lds);
+            } else {
+#pragma unroll
+                for (int i = 0; i < PIPE_PIECES; ++i) {
+                    const int m0 = tok0 + 16 * i + 4 * g;
+                    if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, lut_lds);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PIPE_PIECES; ++i) acc[i] = (v4i){init, init, init, init};
+    };
+    const bool reload = a.nseg > 2;   // otherwise set q % 2 always holds segment q % nseg
+
+    x_issue(0);
+    w_issue(0, A0, I0, n0);
+    x_commit(0);
+    wait_global_loads();
+    __syncthreads();
+    for (int p = 0; p < total; p += 2) {
+        {   // even phase: register set 0, LDS buffer 0
+            const bool nxt = p + 1 < total;
+            if (nxt) {
+                x_issue(p + 1);
+                if (reload || p + 1 < 2) w_issue(p + 1, A1, I1, n1);
+            }
+            multiply(p, A0, I0, n0);
+            finish(p);
+            if (nxt) x_commit(p + 1);
+            wait_global_loads();
+            __syncthreads();
+        }
+        if (p + 1 >= total) break;
+        {   // odd phase: register set 1, LDS buffer 1
+            const bool nxt = p + 2 < total;
+            if (nxt) {
+                x_issue(p + 2);
+                if (reload) w_issue(p + 2, A0, I0, n0);
+            }
+            multiply(p + 1, A1, I1, n1);
+            finish(p + 1);
+            if (nxt) x_commit(p + 2);
+            wait_global_loads();
+            __syncthreads();
+        }
+    }
+}
+
+// =======================================================================================
+// Simple kernel (token tile 64, no software pipelining): kept as an independent second
+// implementation of the same layout; selected with spmm_set_tuning(h, 64, R).  Two
+// different tilings must agree bit for bit because int32 accumulation is order-free.
+// =======================================================================================
+template <int TM, int NW, int R, int OUT, int POST>
+__global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const KernelArgs a)
+{
+    constexpr int STRIDE = TM + 16;
+    constexpr int PIECES = TM / 16;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[SEGMENT_ROWS * STRIDE];
+
     const int b = blockIdx.x;
     const int xcd = b & 7, local = b >> 3;
     const int tt = xcd + 8 * (local / a.n_row_groups);
@@ -133,8 +402,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     const int g = lane >> 4, c = lane & 15;
     const int tok0 = tt * TM;
 
-    // accumulators start at 128 * rowsum(W) of this lane's output row (activations are x - 128)
-    v4i acc[R][C::PIECES];
+    v4i acc[R][PIECES];
     int row_of[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -143,64 +411,41 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         int init = 0;
         if (tile < a.ntiles) init = a.rowsum[row_of[r]] * a.corr_mul;
 #pragma unroll
-        for (int i = 0; i < C::PIECES; ++i) acc[r][i] = (v4i){init, init, init, init};
+        for (int i = 0; i < PIECES; ++i) acc[r][i] = (v4i){init, init, init, init};
     }
 
     for (int seg = 0; seg < a.nseg; ++seg) {
-        // ---- stage activations X[seg*kc .. +rows][tok0 .. tok0+TM) into LDS as (x - 128)
         const int k0 = seg * a.kc;
         const int rows = min(a.kc, a.K - k0);
         if (seg > 0) __syncthreads();
-        for (int p = tid; p < rows * C::PIECES; p += NW * 64) {
-            const int row = p / C::PIECES, piece = p % C::PIECES;
-            const int col = tok0 + piece * 16;
-            const uint8_t* src = a.X + (int64_t)(k0 + row) * a.ldx + col;
-            v4i v;
-            if (a.x_vec_ok && col + 16 <= a.M) {
-                v = *(const v4i*)src;
-            } else {
-                uint32_t w[4] = {0, 0, 0, 0};
-                for (int j = 0; j < 16; ++j)
-                    if (col + j < a.M) w[j >> 2] |= (uint32_t)src[j] << (8 * (j & 3));
-                v = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
-            }
-            v ^= (v4i){(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
-            *(v4i*)(lds + row * C::STRIDE + piece * 16) = v;
+        for (int p = tid; p < rows * PIECES; p += NW * 64) {
+            const int row = p / PIECES, piece = p % PIECES;
+            const v4i v = load_x16(a, k0 + row, tok0 + piece * 16);
+            *(v4i*)(lds + row * STRIDE + piece * 16) = v ^ (v4i){FLIP, FLIP, FLIP, FLIP};
         }
         __syncthreads();
-
-        // ---- multiply: every wave streams the steps of its row tiles for this segment
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int tile = (rg * NW + wave) * R + r;
             if (tile >= a.ntiles) continue;
             const int s0 = a.seg_ptr[tile * a.nseg + seg];
             const int s1 = a.seg_ptr[tile * a.nseg + seg + 1];
-            if (s0 >= s1) continue;
-            v4i w = *(const v4i*)(a.vals + (int64_t)s0 * STEP_VAL_BYTES + lane * 16);
-            uint32_t ix = a.idx[(int64_t)s0 * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
             for (int s = s0; s < s1; ++s) {
-                const v4i w_cur = w;
-                const uint32_t ix_cur = ix;
-                if (s + 1 < s1) {   // prefetch the next step's weights and indices
-                    w = *(const v4i*)(a.vals + (int64_t)(s + 1) * STEP_VAL_BYTES + lane * 16);
-                    ix = a.idx[(int64_t)(s + 1) * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
-                }
-                // this lane supplies the address of list slot 16g + c/2 (and + 8), half c & 1
-                const uint32_t a0 = (ix_cur & 0xffffu) * C::STRIDE + (c & 1) * 8;
-                const uint32_t a1 = (ix_cur >> 16) * C::STRIDE + (c & 1) * 8;
+                const v4i w = *(const v4i*)(a.vals + (int64_t)s * STEP_VAL_BYTES + lane * 16);
+                const uint32_t ix = a.idx[(int64_t)s * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
+                const uint32_t a0 = (ix & 0xffffu) * STRIDE + (c & 1) * 8;
+                const uint32_t a1 = (ix >> 16) * STRIDE + (c & 1) * 8;
 #pragma unroll
-                for (int i = 0; i < C::PIECES; ++i) {
+                for (int i = 0; i < PIECES; ++i) {
                     const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0 + 16 * i));
                     const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1 + 16 * i));
                     const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
-                    acc[r][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, w_cur, acc[r][i], 0, 0, 0);
+                    acc[r][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, w, acc[r][i], 0, 0, 0);
                 }
             }
         }
     }
 
-    // ---- post-operators on the accumulators (registers), then store
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int n = row_of[r];
@@ -211,9 +456,9 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
             if (a.bias) bias = a.bias[n];
         }
 #pragma unroll
-        for (int i = 0; i < C::PIECES; ++i) {
+        for (int i = 0; i < PIECES; ++i) {
             const int m0 = tok0 + 16 * i + 4 * g;
-            if (m0 < a.M) finish4<OUT, POST>(a, acc[r][i], s, bias, n, m0);
+            if (m0 < a.M) finish4<OUT, POST>(a, acc[r][i], s, bias, n, m0, a.lut);
         }
     }
 }
@@ -223,56 +468,107 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
 // ---------------------------------------------------------------------------------------
 bool plan_supported(int token_tile, int row_tiles_per_wave)
 {
+    if (token_tile == 128) return row_tiles_per_wave == 1 || row_tiles_per_wave == 8 || row_tiles_per_wave == 16;
     return (token_tile == 64) && (row_tiles_per_wave == 1 || row_tiles_per_wave == 2);
 }
 
-Plan make_plan(int64_t N, int64_t K, int64_t M, int ntiles, spmm_out_t out_type, int force_tm, int force_r)
+Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int force_r)
 {
-    (void)N; (void)K; (void)out_type;
-    Plan p;
-    p.token_tile = force_tm ? force_tm : 64;
-    p.waves = 8;
-    p.row_tiles_per_wave = force_r ? force_r : ((ntiles >= 64) ? 2 : 1);
-    const int64_t n_tok = (M + p.token_tile - 1) / p.token_tile;
-    const int64_t n_rg = (ntiles + p.waves * p.row_tiles_per_wave - 1) / (p.waves * p.row_tiles_per_wave);
-    p.workgroups = 8 * n_rg * ((n_tok + 7) / 8);
+    Plan p{};
+    p.token_tile = force_tm ? force_tm : PIPE_TM;
+    if (p.token_tile == PIPE_TM) {
+        // up to 4 steps per segment fit the 128-register budget of 16 waves; denser weights run
+        // with 8 waves (256 registers) and half as many rows per workgroup
+        p.max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? 6 : 8);
+        p.waves = (p.max_steps == 4) ? 16 : 8;
+        if (force_r == 8 || force_r == 16) p.waves = (force_r == 16 && p.max_steps != 4) ? 8 : force_r;
+        p.row_tiles_per_wave = 1;
+        p.n_tok_tiles = (int)((M + PIPE_TM - 1) / PIPE_TM);
+        p.n_row_groups = (ntiles + p.waves - 1) / p.waves;
+        // one workgroup per CU: S token-tile streams per row group
+        int S = num_cus / p.n_row_groups;
+        if (S < 1) S = 1;
+        if (S > p.n_tok_tiles) S = p.n_tok_tiles;
+        if (S >= 8) S -= S % 8;
+        p.n_streams = S;
+        p.xcd_map = (S % 8 == 0) ? 1 : 0;
+        p.workgroups = (int64_t)p.n_row_groups * S;
+    } else {
+        p.waves = 8;
+        p.row_tiles_per_wave = force_r ? force_r : 1;
+        p.max_steps = 0;
+        p.n_tok_tiles = (int)((M + p.token_tile - 1) / p.token_tile);
+        p.n_row_groups = (ntiles + p.waves * p.row_tiles_per_wave - 1) / (p.waves * p.row_tiles_per_wave);
+        p.n_streams = 0;
+        p.xcd_map = 1;
+        p.workgroups = (int64_t)8 * p.n_row_groups * ((p.n_tok_tiles + 7) / 8);
+    }
     return p;
 }
 
-template <int TM, int NW, int R>
-static int launch_tmr(const Plan& plan, const KernelArgs& a, spmm_out_t out_type, spmm_postop_t postop, hipStream_t st)
+template <int NW, int MAXS>
+struct PipeLaunch {
+    template <int OUT, int POST>
+    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
+    {
+        hipLaunchKernelGGL((spmm_rowtile_mfma<NW, MAXS, OUT, POST>), grid, block, 0, st, a);
+    }
+};
+
+template <int R>
+struct SimpleLaunch {
+    template <int OUT, int POST>
+    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
+    {
+        hipLaunchKernelGGL((spmm_rowtile_mfma_simple<64, 8, R, OUT, POST>), grid, block, 0, st, a);
+    }
+};
+
+template <class L>
+static void dispatch_epilogue(spmm_out_t out_type, spmm_postop_t postop, dim3 grid, dim3 block, hipStream_t st,
+                              const KernelArgs& a)
 {
-    const dim3 grid((unsigned)plan.workgroups), block(NW * 64);
-#define SPMM_LAUNCH(OUT, POST) \
-    hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, R, OUT, POST>), grid, block, 0, st, a)
     const bool gelu = (postop == SPMM_POST_GELU);
     switch (out_type) {
-    case SPMM_OUT_S32: SPMM_LAUNCH(SPMM_OUT_S32, SPMM_POST_NONE); break;
+    case SPMM_OUT_S32: L::template go<SPMM_OUT_S32, SPMM_POST_NONE>(grid, block, st, a); break;
     case SPMM_OUT_F32:
-        if (gelu) SPMM_LAUNCH(SPMM_OUT_F32, SPMM_POST_GELU); else SPMM_LAUNCH(SPMM_OUT_F32, SPMM_POST_NONE);
+        if (gelu) L::template go<SPMM_OUT_F32, SPMM_POST_GELU>(grid, block, st, a);
+        else L::template go<SPMM_OUT_F32, SPMM_POST_NONE>(grid, block, st, a);
         break;
     case SPMM_OUT_S8:
-        if (gelu) SPMM_LAUNCH(SPMM_OUT_S8, SPMM_POST_GELU); else SPMM_LAUNCH(SPMM_OUT_S8, SPMM_POST_NONE);
+        if (gelu) L::template go<SPMM_OUT_S8, SPMM_POST_GELU>(grid, block, st, a);
+        else L::template go<SPMM_OUT_S8, SPMM_POST_NONE>(grid, block, st, a);
         break;
     case SPMM_OUT_U8:
-        if (gelu) SPMM_LAUNCH(SPMM_OUT_U8, SPMM_POST_GELU); else SPMM_LAUNCH(SPMM_OUT_U8, SPMM_POST_NONE);
+        if (gelu) L::template go<SPMM_OUT_U8, SPMM_POST_GELU>(grid, block, st, a);
+        else L::template go<SPMM_OUT_U8, SPMM_POST_NONE>(grid, block, st, a);
         break;
     }
-#undef SPMM_LAUNCH
-    return (int)hipGetLastError();
 }
 
 int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_postop_t postop, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const int rows_per_wg = plan.waves * plan.row_tiles_per_wave;
-    a.n_tok_tiles = (int)((a.M + plan.token_tile - 1) / plan.token_tile);
-    a.n_row_groups = (a.ntiles + rows_per_wg - 1) / rows_per_wg;
-    if (plan.token_tile == 64 && plan.waves == 8) {
-        if (plan.row_tiles_per_wave == 1) return launch_tmr<64, 8, 1>(plan, a, out_type, postop, st);
-        if (plan.row_tiles_per_wave == 2) return launch_tmr<64, 8, 2>(plan, a, out_type, postop, st);
+    a.n_tok_tiles = plan.n_tok_tiles;
+    a.n_row_groups = plan.n_row_groups;
+    a.n_streams = plan.n_streams;
+    a.xcd_map = plan.xcd_map;
+    const dim3 grid((unsigned)plan.workgroups), block((unsigned)plan.waves * 64);
+    if (plan.token_tile == PIPE_TM) {
+        if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
+        if (plan.waves == 16 && plan.max_steps == 4) dispatch_epilogue<PipeLaunch<16, 4>>(out_type, postop, grid, block, st, a);
+        else if (plan.waves == 8 && plan.max_steps == 4) dispatch_epilogue<PipeLaunch<8, 4>>(out_type, postop, grid, block, st, a);
+        else if (plan.waves == 8 && plan.max_steps == 6) dispatch_epilogue<PipeLaunch<8, 6>>(out_type, postop, grid, block, st, a);
+        else if (plan.waves == 8 && plan.max_steps == 8) dispatch_epilogue<PipeLaunch<8, 8>>(out_type, postop, grid, block, st, a);
+        else return (int)hipErrorInvalidValue;
+    } else if (plan.token_tile == 64 && plan.waves == 8 && plan.row_tiles_per_wave == 1) {
+        dispatch_epilogue<SimpleLaunch<1>>(out_type, postop, grid, block, st, a);
+    } else if (plan.token_tile == 64 && plan.waves == 8 && plan.row_tiles_per_wave == 2) {
+        dispatch_epilogue<SimpleLaunch<2>>(out_type, postop, grid, block, st, a);
+    } else {
+        return (int)hipErrorInvalidValue;
     }
-    return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
 }
 
 }  // namespace spmm

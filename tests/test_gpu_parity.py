@@ -120,12 +120,15 @@ def test_config4_large_full_size(case):
     check_case(case)
 
 
-def test_config4_large_both_tunings_agree_bitwise():
+def test_config4_large_all_kernel_variants_agree_bitwise():
+    # int32 accumulation is order-free: the pipelined kernel (token tile 128) and the simple
+    # kernel (token tile 64, one or two row tiles per wave) must give identical bytes
     case = wl.large_cases()[0]
     d = wl.make(case)
-    a, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=(64, 1))
-    b, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=(64, 2))
-    assert np.array_equal(a, b)
+    a, _ = gpu_spmm(d["W"], d["X"], d, case)
+    b, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=(64, 1))
+    c, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=(64, 2))
+    assert np.array_equal(a, b) and np.array_equal(a, c)
 
 
 # ---------------------------------------------------------------------------- config 5 (sample of the grid)
@@ -149,10 +152,20 @@ def test_config5_grid_sample_s32_and_s8(case):
     (260, 100, 257), (5, 3000, 7),
 ])
 @pytest.mark.parametrize("out_type", ["s32", "s8"])
-def test_ragged_shapes(N, K, M, out_type):
+@pytest.mark.parametrize("tuning", [None, (64, 2)], ids=["pipelined", "simple"])
+def test_ragged_shapes(N, K, M, out_type, tuning):
     case = wl.Case("ragged", N, K, M, 0.6, wl.N4K1, out_type, "none", keys=(60, N, K, M))
-    check_case(case)
-    check_case(case.with_(orientation=wl.N1K4))
+    check_case(case, tuning=tuning)
+    check_case(case.with_(orientation=wl.N1K4), tuning=tuning)
+
+
+@pytest.mark.parametrize("N,K,M,s", [(300, 1100, 700, 0.9), (256, 1536, 1300, 0.8), (272, 512, 2100, 0.7),
+                                     (64, 3000, 513, 0.5), (1024, 256, 4100, 0.0)])
+def test_many_token_tiles_and_segments(N, K, M, s):
+    """Several token tiles per workgroup stream, 1 / 2 / 3+ K segments (resident and
+    re-streamed weights), ragged last tile, every step-count variant of the kernel."""
+    for ot, po in (("s32", "none"), ("s8", "gelu")):
+        check_case(wl.Case("multi", N, K, M, s, wl.N4K1, ot, po, keys=(66, N, K, M)))
 
 
 @pytest.mark.parametrize("out_type,postop", [("s32", "none"), ("f32", "none"), ("f32", "gelu"),
