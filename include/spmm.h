@@ -122,8 +122,9 @@ spmm_status_t spmm_layout_dims(const spmm_handle_t *h, int32_t *tile_rows, int32
 /* Copy the compressed layout into HOST buffers sized from spmm_layout_dims (NULL = skip):
  *   vals    uint8 [n_steps][64 lanes][16]  weight of row (lane % 16) at list slot 16*(lane/16)+t
  *   idx     uint32 [n_steps][32]           entry 8g+t = k_local[16g+t] | k_local[16g+8+t] << 16,
- *                                           k_local relative to the segment start; padding
- *                                           slots have zero weights and index 0
+ *                                           k_local relative to the segment start, in an
+ *                                           order chosen for LDS banking; padding slots
+ *                                           have zero weights and a valid row index
  *   seg_ptr int32 [n_tiles*n_segments + 1] first step of (tile, segment), CSR style
  *   rowsum  int32 [n_tiles*tile_rows]      sum over k of each (padded) row of W */
 spmm_status_t spmm_layout_export(const spmm_handle_t *h, uint8_t *vals_host, uint32_t *idx_host,
@@ -155,6 +156,9 @@ spmm_status_t spmm_plan(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
                         int32_t *token_tile, int32_t *rows_per_workgroup, int64_t *workgroups);
 
 /* Override the automatic choice for later spmm_run calls on this handle (0 = automatic).
+ * token_tile 128 selects the pipelined kernels (row_tiles_per_wave 1, 8 or 16 = waves per
+ * workgroup, 2 = fused variant; a variant that cannot hold the weight's densest segment falls
+ * back to the automatic one), token_tile 64 the simple kernel (1 or 2 row tiles per wave).
  * Unsupported values return SPMM_E_UNSUPPORTED and change nothing.  Not thread-safe
  * against concurrent spmm_run on the same handle. */
 spmm_status_t spmm_set_tuning(spmm_handle_t *h, int32_t token_tile, int32_t row_tiles_per_wave);

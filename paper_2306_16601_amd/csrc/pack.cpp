@@ -110,6 +110,77 @@ static void expand_tile(const Bsr& b, int64_t tile, std::vector<int8_t>& buf)
     }
 }
 
+// Order the listed k of one (row tile, segment) inside its steps so that the transposing
+// LDS reads hit distinct banks.
+//
+// One ds_read_b64_tr_b8 of a wave touches 32 activation rows (4 lane groups x 8 rows), 16 bytes
+// each; with the row pitch used by the kernels (token tile + 16 bytes) a row starts at LDS
+// bank 4 * ((9 * row) % 16), so two rows collide exactly when their indices are congruent
+// mod 16.  The 64 slots of a step are read by two instructions (slots t < 8 and t >= 8 of
+// every group), each in two half-waves (groups {0,1} and {2,3}): four "half-reads" of 16 rows.
+// The entries are dealt out so that a half-read holds every residue mod 16 at most once
+// whenever the counts allow it; padding slots (zero weights) are pointed at a row of a
+// residue the half-read still lacks instead of all hitting row 0.
+// slot_k[s*64 + 16*g + t] = segment-local k or -1 (padding); slot_row = row actually read.
+static void arrange_for_lds_banks(const std::vector<int32_t>& list, int rows_in_segment, int nsteps,
+                                  std::vector<int32_t>& slot_k, std::vector<int32_t>& slot_row)
+{
+    const int H = 4 * nsteps;   // half-reads
+    slot_k.assign((size_t)nsteps * STEP_K, -1);
+    slot_row.assign((size_t)nsteps * STEP_K, 0);
+    if (nsteps == 0) return;
+    std::vector<std::vector<int32_t>> by_res(16);
+    for (int32_t k : list) by_res[k & 15].push_back(k);
+    int order[16];
+    for (int r = 0; r < 16; ++r) order[r] = r;
+    std::stable_sort(order, order + 16, [&](int x, int y) { return by_res[x].size() > by_res[y].size(); });
+
+    // Largest residue class first; each class is spread over the least-filled half-reads, one
+    // entry per half-read, so that no half-read runs out of room while others still have
+    // holes.  Only a class with more than H entries is forced to double up somewhere.
+    std::vector<std::vector<int32_t>> hr((size_t)H);
+    std::vector<uint32_t> mask((size_t)H, 0);
+    std::vector<int> by_load((size_t)H);
+    for (int oi = 0; oi < 16; ++oi) {
+        const int r = order[oi];
+        size_t next = 0;
+        while (next < by_res[r].size()) {
+            for (int h = 0; h < H; ++h) by_load[h] = h;
+            std::stable_sort(by_load.begin(), by_load.end(),
+                             [&](int x, int y) { return hr[x].size() < hr[y].size(); });
+            bool placed = false;
+            for (int i = 0; i < H && next < by_res[r].size(); ++i) {
+                const int h = by_load[i];
+                if (hr[h].size() >= 16) break;
+                hr[h].push_back(by_res[r][next++]);
+                mask[h] |= 1u << r;
+                placed = true;
+            }
+            if (!placed) break;   // cannot happen: 16 * H slots >= list.size()
+        }
+    }
+    for (int h = 0; h < H; ++h) {
+        const int s = h / 4, instr = (h / 2) % 2, pair = h % 2;
+        int next_res = 0;
+        for (int j = 0; j < 16; ++j) {
+            const int g = 2 * pair + j / 8, t = 8 * instr + j % 8;
+            const size_t slot = (size_t)s * STEP_K + 16 * g + t;
+            if (j < (int)hr[h].size()) {
+                slot_k[slot] = hr[h][j];
+                slot_row[slot] = hr[h][j];
+            } else {
+                while (next_res < 16 && (mask[h] & (1u << next_res))) ++next_res;
+                int row = 0;
+                if (next_res < 16) {
+                    if (next_res < rows_in_segment) row = next_res;
+                    mask[h] |= 1u << next_res;
+                }
+                slot_row[slot] = row;
+            }
+        }
+    }
+}
+
 void layout_from_bsr(const Bsr& b, int kc, HostLayout& out)
 {
     const int64_t N = b.N, K = b.K;
@@ -124,7 +195,7 @@ void layout_from_bsr(const Bsr& b, int kc, HostLayout& out)
     out.max_steps_per_segment = 0;
 
     std::vector<int8_t> buf((size_t)TILE_ROWS * K);
-    std::vector<int32_t> list;
+    std::vector<int32_t> list, slot_k, slot_row;
     for (int64_t tile = 0; tile < out.ntiles; ++tile) {
         expand_tile(b, tile, buf);
         for (int r = 0; r < TILE_ROWS; ++r) {
@@ -142,27 +213,23 @@ void layout_from_bsr(const Bsr& b, int kc, HostLayout& out)
                 if (any) list.push_back((int32_t)(k - k_lo));
             }
             const int nsteps = (int)((list.size() + STEP_K - 1) / STEP_K);
+            arrange_for_lds_banks(list, (int)(k_hi - k_lo), nsteps, slot_k, slot_row);
             for (int s = 0; s < nsteps; ++s) {
                 const size_t vbase = out.vals.size(), ibase = out.idx.size();
                 out.vals.resize(vbase + STEP_VAL_BYTES, 0);
                 out.idx.resize(ibase + STEP_IDX_DWORDS, 0);
-                auto slot_k = [&](int slot) -> int32_t {   // segment-local k of list slot, -1 = padding
-                    const size_t e = (size_t)s * STEP_K + slot;
-                    return e < list.size() ? list[e] : -1;
-                };
+                const int32_t* sk = &slot_k[(size_t)s * STEP_K];     // segment-local k, -1 = padding
+                const int32_t* sr = &slot_row[(size_t)s * STEP_K];   // activation row the slot reads
                 for (int lane = 0; lane < 64; ++lane) {
                     const int g = lane / 16, r = lane % 16;
                     for (int t = 0; t < 16; ++t) {
-                        const int32_t kl = slot_k(16 * g + t);
+                        const int32_t kl = sk[16 * g + t];
                         if (kl >= 0) out.vals[vbase + (size_t)lane * 16 + t] = (uint8_t)buf[(size_t)r * K + k_lo + kl];
                     }
                 }
                 for (int g = 0; g < 4; ++g)
-                    for (int t = 0; t < 8; ++t) {
-                        const int32_t ka = std::max(0, slot_k(16 * g + t));
-                        const int32_t kb = std::max(0, slot_k(16 * g + 8 + t));
-                        out.idx[ibase + 8 * g + t] = (uint32_t)ka | ((uint32_t)kb << 16);
-                    }
+                    for (int t = 0; t < 8; ++t)
+                        out.idx[ibase + 8 * g + t] = (uint32_t)sr[16 * g + t] | ((uint32_t)sr[16 * g + 8 + t] << 16);
             }
             steps_this_tile += nsteps;
             out.max_steps_per_segment = std::max(out.max_steps_per_segment, nsteps);

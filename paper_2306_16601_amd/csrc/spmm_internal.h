@@ -24,7 +24,8 @@ namespace spmm {
 // supplies the LDS address of list slot 16g+t (first transposing read) and 16g+8+t (second)
 // finds both in one dword:
 //     idx[step][8*g + t] = k_local[16g + t] | k_local[16g + 8 + t] << 16,   g < 4, t < 8
-// Padding slots carry zero weights and index 0 (always resident), so they add nothing.
+// Padding slots carry zero weights and the index of some resident row, so they add nothing.
+// Inside a step the listed k are ordered for conflict-free LDS banks, not ascending (pack.cpp).
 // ---------------------------------------------------------------------------------------
 constexpr int TILE_ROWS = 16;
 constexpr int STEP_K = 64;

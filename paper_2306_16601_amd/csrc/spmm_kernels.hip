@@ -34,6 +34,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "spmm_internal.h"
 
@@ -151,50 +152,83 @@ constexpr int PIPE_TM = 128;
 constexpr int PIPE_STRIDE = PIPE_TM + 16;                   // 144 B: consecutive rows start 4 banks apart
 constexpr int PIPE_BUF_BYTES = SEGMENT_ROWS * PIPE_STRIDE;  // 73728 B
 constexpr int PIPE_PIECES = PIPE_TM / 16;                   // 8 MFMA token sub-tiles
-constexpr int PIPE_LDS = 2 * PIPE_BUF_BYTES + 256;
+constexpr int PIPE_LUT = 0;                                 // table of Algorithm 2 at LDS offset 0: the key is the address
+constexpr int PIPE_X0 = 256;                                // activation buffers behind it (two, back to back)
+constexpr int PIPE_LDS = PIPE_X0 + 2 * PIPE_BUF_BYTES;
+// Output staging for 1-byte outputs.  Every LDS row has 16 spare bytes behind its 128 tokens
+// (1024 such chunks over both buffers); wave w transposes its 16 rows x 64 tokens through
+// chunks 64w .. 64w+63 so that a row's tokens leave in 64-byte runs instead of 4-byte pieces.
+// Staging row r, 16-token piece j lives in chunk 4r + (j ^ (r >> 2)): with the 144-byte pitch
+// both the 4-byte writes and the 16-byte reads then touch every LDS bank exactly once.
+constexpr int PIPE_PAD0 = PIPE_X0 + PIPE_TM;
 
 // Post-operators + store for one full token tile of one wave, everything in bounds and
-// aligned: lane (g, c) holds tokens tok0 + 16 i + 4 g + {0..3} of output row n.
+// aligned: lane (g, c) holds tokens tok0 + 16 i + 4 g + {0..3} of output row 16 * tile + c.
+// 4-byte outputs are stored straight from the accumulator layout (16 bytes per lane, 64-byte
+// runs per row); 1-byte outputs go through the LDS staging chunks described above.
 template <int OUT, int POST>
 __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i (&acc)[PIPE_PIECES], const float scale,
-                                                 const float bias, const int n, const int tok, const uint8_t* lut_lds)
+                                                 const float bias, const int tile, const int tok0, int lane,
+                                                 const int wave, uint8_t* lds)
 {
+    // Keep the address arithmetic below local to the epilogue: without this the compiler hoists
+    // it out of the phase loop and the long-lived results push the kernel into register spills.
+    asm volatile("" : "+v"(lane));
+    const int g = lane >> 4, c = lane & 15;
     if constexpr (OUT == SPMM_OUT_S32) {
-        int32_t* o = (int32_t*)a.out + ((int64_t)n * a.ldo + tok);
+        int32_t* o = (int32_t*)a.out + ((int64_t)(tile * TILE_ROWS + c) * a.ldo + tok0 + 4 * g);
+        if (tile * TILE_ROWS + c < a.N) {
 #pragma unroll
-        for (int i = 0; i < PIPE_PIECES; ++i) *(v4i*)(o + 16 * i) = acc[i];
+            for (int i = 0; i < PIPE_PIECES; ++i) *(v4i*)(o + 16 * i) = acc[i];
+        }
     } else if constexpr (OUT == SPMM_OUT_F32) {
-        float* o = (float*)a.out + ((int64_t)n * a.ldo + tok);
+        float* o = (float*)a.out + ((int64_t)(tile * TILE_ROWS + c) * a.ldo + tok0 + 4 * g);
+        if (tile * TILE_ROWS + c < a.N) {
 #pragma unroll
-        for (int i = 0; i < PIPE_PIECES; ++i) {
-            v4f y;
+            for (int i = 0; i < PIPE_PIECES; ++i) {
+                v4f y;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                y[r] = __fmaf_rn((float)acc[i][r], scale, bias);
-                if constexpr (POST == SPMM_POST_GELU) y[r] = gelu_f32(y[r]);
+                for (int r = 0; r < 4; ++r) {
+                    y[r] = __fmaf_rn((float)acc[i][r], scale, bias);
+                    if constexpr (POST == SPMM_POST_GELU) y[r] = gelu_f32(y[r]);
+                }
+                *(v4f*)(o + 16 * i) = y;
             }
-            *(v4f*)(o + 16 * i) = y;
         }
     } else {
-        uint8_t* o = (uint8_t*)a.out + ((int64_t)n * a.ldo + tok);
+        // write side: this lane's quad of piece j goes to staging row c, piece j
+        const uint32_t wbase = PIPE_PAD0 + (uint32_t)(64 * wave + 4 * c) * PIPE_STRIDE + 4 * g;
+        const int wsw = c >> 2;
+        // read side: this lane fetches 16 tokens of staging row lane / 4, piece lane % 4
+        const int rr = lane >> 2, rj = lane & 3;
+        const uint32_t raddr = PIPE_PAD0 + (uint32_t)(64 * wave + 4 * rr + (rj ^ (rr >> 2))) * PIPE_STRIDE;
+        const int orow = tile * TILE_ROWS + rr;
+        uint8_t* o = (uint8_t*)a.out + ((int64_t)orow * a.ldo + tok0 + 16 * rj);
 #pragma unroll
-        for (int i = 0; i < PIPE_PIECES; ++i) {
-            uint32_t word = 0;
+        for (int h = 0; h < 2; ++h) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float y = __fmaf_rn((float)acc[i][r], scale, bias);
-                uint32_t q;
-                if constexpr (POST == SPMM_POST_GELU) {
-                    const float t = rintf(y * a.inv_mid) + 128.0f;
-                    q = lut_lds[__builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u)];
-                } else {
-                    const float lo = (OUT == SPMM_OUT_U8) ? 0.0f : -128.0f;
-                    const float hi = (OUT == SPMM_OUT_U8) ? 255.0f : 127.0f;
-                    q = (uint32_t)((int)fminf(hi, fmaxf(lo, rintf(y * a.inv_out) + a.out_zp_f))) & 0xffu;
+            for (int j = 0; j < 4; ++j) {
+                const int i = 4 * h + j;
+                uint32_t word = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float y = __fmaf_rn((float)acc[i][r], scale, bias);
+                    uint32_t q;
+                    if constexpr (POST == SPMM_POST_GELU) {
+                        // key = sat_s8(rint(y / mid_scale)) + 128; v_cvt_pk_u8_f32 saturates to [0, 255]
+                        const float t = rintf(y * a.inv_mid) + 128.0f;
+                        q = lds[PIPE_LUT + __builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u)];
+                    } else {
+                        const float lo = (OUT == SPMM_OUT_U8) ? 0.0f : -128.0f;
+                        const float hi = (OUT == SPMM_OUT_U8) ? 255.0f : 127.0f;
+                        q = (uint32_t)((int)fminf(hi, fmaxf(lo, rintf(y * a.inv_out) + a.out_zp_f))) & 0xffu;
+                    }
+                    word |= q << (8 * r);
                 }
-                word |= q << (8 * r);
+                *(uint32_t*)(lds + wbase + (uint32_t)(j ^ wsw) * PIPE_STRIDE) = word;
             }
-            *(uint32_t*)(o + 16 * i) = word;
+            const v4i v = *(const v4i*)(lds + raddr);   // same wave: LDS operations complete in order
+            if (orow < a.N) *(v4i*)(o + 64 * h) = v;
         }
     }
 }
@@ -205,7 +239,6 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     constexpr int NTHREADS = NW * 64;
     constexpr int XLOADS = SEGMENT_ROWS * PIPE_PIECES / NTHREADS;   // 16-byte loads per thread and phase
     __shared__ __attribute__((aligned(16))) uint8_t lds[PIPE_LDS];
-    uint8_t* const lut_lds = lds + 2 * PIPE_BUF_BYTES;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -242,7 +275,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         }
     }
     if constexpr (POST == SPMM_POST_GELU && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8)) {
-        if (tid < 256) lut_lds[tid] = (uint8_t)a.lut[tid];
+        if (tid < 256) lds[PIPE_LUT + tid] = (uint8_t)a.lut[tid];
     }
 
     v4i A0[MAXS], A1[MAXS];
@@ -255,7 +288,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
 
     // per-thread staging coordinates: XLOADS rows (NTHREADS / 8 apart), one 16-byte piece
     const int x_row0 = tid >> 3, x_piece = tid & 7;
-    const uint32_t x_lds0 = (uint32_t)x_row0 * PIPE_STRIDE + x_piece * 16;
+    const uint32_t x_lds0 = PIPE_X0 + (uint32_t)x_row0 * PIPE_STRIDE + x_piece * 16;
 
     // ---- global loads of the activations of phase q into registers.  The common case (16-byte
     // aligned rows, full token tile) is branch-free so that all loads are in flight together;
@@ -306,7 +339,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     };
     // ---- multiply phase q: gather + transpose out of LDS, 8 matrix instructions per step
     auto multiply = [&](const int q, const v4i (&A)[MAXS], const uint32_t (&I)[MAXS], const int cnt) {
-        const uint32_t base = (uint32_t)(q & 1) * PIPE_BUF_BYTES + (c & 1) * 8;
+        const uint32_t base = PIPE_X0 + (uint32_t)(q & 1) * PIPE_BUF_BYTES + (c & 1) * 8;
 #pragma unroll
         for (int s = 0; s < MAXS; ++s) {
             if (s < cnt) {
@@ -328,14 +361,14 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         const int j = q / a.nseg;
         if (q - j * a.nseg != a.nseg - 1) return;
         const int tok0 = (stream + j * S) * PIPE_TM;
-        if (have_tile && n < a.N) {
+        if (have_tile) {
             if (a.out_vec_ok && tok0 + PIPE_TM <= a.M) {
-                finish_tile_fast<OUT, POST>(a, acc, scale, bias, n, tok0 + 4 * g, lut_lds);
-            } else {
+                finish_tile_fast<OUT, POST>(a, acc, scale, bias, tile, tok0, lane, wave, lds);
+            } else if (n < a.N) {
 #pragma unroll
                 for (int i = 0; i < PIPE_PIECES; ++i) {
                     const int m0 = tok0 + 16 * i + 4 * g;
-                    if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, lut_lds);
+                    if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, lds + PIPE_LUT);
                 }
             }
         }
@@ -357,9 +390,9 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
                 if (reload || p + 1 < 2) w_issue(p + 1, A1, I1, n1);
             }
             multiply(p, A0, I0, n0);
-            finish(p);
             if (nxt) x_commit(p + 1);
-            wait_global_loads();
+            wait_global_loads();   // before the output stores: they must not be waited for
+            finish(p);
             __syncthreads();
         }
         if (p + 1 >= total) break;
@@ -370,10 +403,306 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
                 if (reload) w_issue(p + 2, A0, I0, n0);
             }
             multiply(p + 1, A1, I1, n1);
+            if (nxt) x_commit(p + 2);
+            wait_global_loads();
             finish(p + 1);
+            __syncthreads();
+        }
+    }
+}
+
+// =======================================================================================
+// Fused variant: 8 waves per workgroup, two row tiles (A, B) per wave, post-operators of one
+// tile interleaved with the matrix instructions of the other.
+//
+// The post-operator chain is pure VALU work (about 8 instructions per output) while the
+// multiply is LDS + matrix-core work; run one after the other they leave each unit idle
+// half of the time.  Here every phase is  [multiply A | finish B of the previous token
+// tile]  then  [multiply B | finish A if this was the last segment], written as one
+// instruction stream per wave so that the VALU slices fill the shadow of the matrix
+// instructions and of the LDS latency.  Same LDS layout and phase pipeline as above.
+// =======================================================================================
+constexpr int FUSED_NW = 8;
+constexpr int FUSED_LUT = PIPE_LUT;
+constexpr int FUSED_X0 = PIPE_X0;
+
+// post-operators for 4 consecutive tokens (one accumulator quad) in the aligned fast path
+template <int OUT, int POST>
+__device__ __forceinline__ void finish_quad(const KernelArgs& a, const v4i acc, const float scale, const float bias,
+                                            uint8_t* optr, const int piece, const uint8_t* lds)
+{
+    if constexpr (OUT == SPMM_OUT_S32) {
+        *(v4i*)((int32_t*)optr + 16 * piece) = acc;
+    } else if constexpr (OUT == SPMM_OUT_F32) {
+        v4f y;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            y[r] = __fmaf_rn((float)acc[r], scale, bias);
+            if constexpr (POST == SPMM_POST_GELU) y[r] = gelu_f32(y[r]);
+        }
+        *(v4f*)((float*)optr + 16 * piece) = y;
+    } else {
+        uint32_t word = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float y = __fmaf_rn((float)acc[r], scale, bias);
+            uint32_t q;
+            if constexpr (POST == SPMM_POST_GELU) {
+                const float t = rintf(y * a.inv_mid) + 128.0f;
+                q = lds[FUSED_LUT + __builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u)];
+            } else {
+                const float lo = (OUT == SPMM_OUT_U8) ? 0.0f : -128.0f;
+                const float hi = (OUT == SPMM_OUT_U8) ? 255.0f : 127.0f;
+                q = (uint32_t)((int)fminf(hi, fmaxf(lo, rintf(y * a.inv_out) + a.out_zp_f))) & 0xffu;
+            }
+            word |= q << (8 * r);
+        }
+        *(uint32_t*)(optr + 16 * piece) = word;
+    }
+}
+
+template <int MAXS, int OUT, int POST>
+__global__ void __launch_bounds__(FUSED_NW * 64) spmm_rowtile_mfma_fused(const KernelArgs a)
+{
+    constexpr int NTHREADS = FUSED_NW * 64;
+    constexpr int XLOADS = SEGMENT_ROWS * PIPE_PIECES / NTHREADS;   // 8
+    constexpr int ESZ = (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8) ? 1 : 4;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[FUSED_X0 + 2 * PIPE_BUF_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+
+    int rg, stream;
+    {
+        const int b = blockIdx.x;
+        if (a.xcd_map) {
+            const int local = b >> 3;
+            stream = (b & 7) + 8 * (local / a.n_row_groups);
+            rg = local % a.n_row_groups;
+        } else {
+            rg = b % a.n_row_groups;
+            stream = b / a.n_row_groups;
+        }
+    }
+    const int S = a.n_streams;
+    const int n_my = (a.n_tok_tiles - stream + S - 1) / S;
+    const int total = n_my * a.nseg;
+
+    // the wave's two row tiles
+    const int tileA = (rg * FUSED_NW + wave) * 2, tileB = tileA + 1;
+    const bool haveA = tileA < a.ntiles, haveB = tileB < a.ntiles;
+    const int nA = tileA * TILE_ROWS + c, nB = tileB * TILE_ROWS + c;
+    const int initA = haveA ? a.rowsum[nA] * a.corr_mul : 0;
+    const int initB = haveB ? a.rowsum[nB] * a.corr_mul : 0;
+    float scaleA = 0.0f, biasA = 0.0f, scaleB = 0.0f, biasB = 0.0f;
+    if constexpr (OUT != SPMM_OUT_S32) {
+        if (haveA && nA < a.N) { scaleA = a.w_scale[nA] * a.x_scale; if (a.bias) biasA = a.bias[nA]; }
+        if (haveB && nB < a.N) { scaleB = a.w_scale[nB] * a.x_scale; if (a.bias) biasB = a.bias[nB]; }
+    }
+    if constexpr (POST == SPMM_POST_GELU && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8)) {
+        if (tid < 256) lds[FUSED_LUT + tid] = (uint8_t)a.lut[tid];
+    }
+    const bool storeA = haveA && nA < a.N, storeB = haveB && nB < a.N;
+
+    v4i WA0[MAXS], WA1[MAXS], WB0[MAXS], WB1[MAXS];
+    uint32_t IA0[MAXS], IA1[MAXS], IB0[MAXS], IB1[MAXS];
+    int cA0 = 0, cA1 = 0, cB0 = 0, cB1 = 0;
+    v4i xr[XLOADS];
+    v4i accA[PIPE_PIECES], accB[PIPE_PIECES];
+#pragma unroll
+    for (int i = 0; i < PIPE_PIECES; ++i) {
+        accA[i] = (v4i){initA, initA, initA, initA};
+        accB[i] = (v4i){initB, initB, initB, initB};
+    }
+
+    const int x_row0 = tid >> 3, x_piece = tid & 7;
+    const uint32_t x_lds0 = FUSED_X0 + (uint32_t)x_row0 * PIPE_STRIDE + x_piece * 16;
+
+    auto tok_of = [&](const int q) { return (stream + (q / a.nseg) * S) * PIPE_TM; };
+    auto x_issue = [&](const int q) {
+        const int j = q / a.nseg, seg = q - j * a.nseg;
+        const int tok0 = (stream + j * S) * PIPE_TM;
+        const int k0 = seg * SEGMENT_ROWS;
+        const int last = min(SEGMENT_ROWS, a.K - k0) - 1;
+        if (a.x_vec_ok && tok0 + PIPE_TM <= a.M) {
+            const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0 + x_piece * 16;
+#pragma unroll
+            for (int u = 0; u < XLOADS; ++u) {
+                const int row = min(x_row0 + u * (NTHREADS / 8), last);
+                xr[u] = *(const v4i*)(src + (int64_t)row * a.ldx);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < XLOADS; ++u) {
+                const int row = min(x_row0 + u * (NTHREADS / 8), last);
+                xr[u] = load_x16(a, k0 + row, tok0 + x_piece * 16);
+            }
+        }
+    };
+    auto x_commit = [&](const int q) {
+        uint8_t* buf = lds + (q & 1) * PIPE_BUF_BYTES + x_lds0;
+#pragma unroll
+        for (int u = 0; u < XLOADS; ++u)
+            *(v4i*)(buf + u * (NTHREADS / 8) * PIPE_STRIDE) = xr[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+    };
+    auto w_issue = [&](const int q, const int tile, const bool have, v4i (&W)[MAXS], uint32_t (&I)[MAXS], int& cnt) {
+        cnt = 0;
+        int s0 = 0;
+        if (have) {
+            const int seg = q % a.nseg;
+            s0 = a.seg_ptr[tile * a.nseg + seg];
+            cnt = a.seg_ptr[tile * a.nseg + seg + 1] - s0;
+        }
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) {
+            const int step = (s < cnt) ? s0 + s : 0;
+            W[s] = *(const v4i*)(a.vals + (int64_t)step * STEP_VAL_BYTES + lane * 16);
+            I[s] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
+        }
+    };
+    // multiply one tile for phase q; if FIN, finish the 8 accumulator quads of `fin` on the way
+    // (one quad after every third matrix instruction; quads of skipped steps run in their place)
+    auto mul_fin = [&](auto fin_tag, const int q, const v4i (&W)[MAXS], const uint32_t (&I)[MAXS], const int cnt,
+                       v4i (&acc)[PIPE_PIECES], v4i (&fin)[PIPE_PIECES], const float fscale, const float fbias,
+                       uint8_t* foptr, const int finit) {
+        constexpr bool FIN = decltype(fin_tag)::value;
+        const uint32_t base = FUSED_X0 + (uint32_t)(q & 1) * PIPE_BUF_BYTES + (c & 1) * 8;
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) {
+            if (s < cnt) {
+                const uint32_t a0 = (I[s] & 0xffffu) * PIPE_STRIDE + base;
+                const uint32_t a1 = (I[s] >> 16) * PIPE_STRIDE + base;
+#pragma unroll
+                for (int i = 0; i < PIPE_PIECES; ++i) {
+                    const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0 + 16 * i));
+                    const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1 + 16 * i));
+                    const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
+                    acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, W[s], acc[i], 0, 0, 0);
+                    if constexpr (FIN) {
+                        constexpr int dummy = 0; (void)dummy;
+                        const int m = 8 * s + i;
+                        if (m % 3 == 2 && m / 3 < PIPE_PIECES) {
+                            finish_quad<OUT, POST>(a, fin[m / 3], fscale, fbias, foptr, m / 3, lds);
+                            fin[m / 3] = (v4i){finit, finit, finit, finit};
+                        }
+                    }
+                }
+            } else if constexpr (FIN) {
+#pragma unroll
+                for (int i = 0; i < PIPE_PIECES; ++i) {
+                    const int m = 8 * s + i;
+                    if (m % 3 == 2 && m / 3 < PIPE_PIECES) {
+                        finish_quad<OUT, POST>(a, fin[m / 3], fscale, fbias, foptr, m / 3, lds);
+                        fin[m / 3] = (v4i){finit, finit, finit, finit};
+                    }
+                }
+            }
+        }
+        static_assert(8 * MAXS / 3 >= PIPE_PIECES, "all quads must be scheduled inside the step loop");
+    };
+    // generic (ragged / unaligned) finish of a whole tile, not overlapped
+    auto finish_slow = [&](v4i (&acc)[PIPE_PIECES], const int n, const float scale, const float bias, const int tok0,
+                           const int init) {
+#pragma unroll
+        for (int i = 0; i < PIPE_PIECES; ++i) {
+            const int m0 = tok0 + 16 * i + 4 * g;
+            if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, lds + FUSED_LUT);
+            acc[i] = (v4i){init, init, init, init};
+        }
+    };
+    auto out_ptr = [&](const int n, const int tok0) {
+        return (uint8_t*)a.out + ((int64_t)n * a.ldo + tok0 + 4 * g) * ESZ;
+    };
+    std::true_type FIN_YES;
+    std::false_type FIN_NO;
+
+    const bool reload = a.nseg > 2;
+    // pendB: tile B of token offset pendB_tok still has to be finished (during the next multiply of A)
+    bool pendB = false;
+    int pendB_tok = 0;
+
+    // one phase with register sets (WA, IA, cA) / (WB, IB, cB)
+    auto phase = [&](const int q, const v4i (&WA)[MAXS], const uint32_t (&IA)[MAXS], const int cA,
+                     const v4i (&WB)[MAXS], const uint32_t (&IB)[MAXS], const int cB) {
+        const int j = q / a.nseg;
+        const bool last_seg = (q - j * a.nseg == a.nseg - 1);
+        const int tok0 = (stream + j * S) * PIPE_TM;
+        // ---- part 1: multiply A, finishing B of the previous token tile on the way
+        if (pendB) {
+            const bool fast = a.out_vec_ok && pendB_tok + PIPE_TM <= a.M;
+            if (storeB && fast) {
+                mul_fin(FIN_YES, q, WA, IA, cA, accA, accB, scaleB, biasB, out_ptr(nB, pendB_tok), initB);
+            } else {
+                if (storeB) finish_slow(accB, nB, scaleB, biasB, pendB_tok, initB);
+                mul_fin(FIN_NO, q, WA, IA, cA, accA, accB, 0.0f, 0.0f, nullptr, 0);
+            }
+            pendB = false;
+        } else {
+            mul_fin(FIN_NO, q, WA, IA, cA, accA, accB, 0.0f, 0.0f, nullptr, 0);
+        }
+        // ---- part 2: multiply B, finishing A if this was the last segment
+        if (last_seg) {
+            const bool fast = a.out_vec_ok && tok0 + PIPE_TM <= a.M;
+            if (storeA && fast) {
+                mul_fin(FIN_YES, q, WB, IB, cB, accB, accA, scaleA, biasA, out_ptr(nA, tok0), initA);
+            } else {
+                mul_fin(FIN_NO, q, WB, IB, cB, accB, accA, 0.0f, 0.0f, nullptr, 0);
+                if (storeA) finish_slow(accA, nA, scaleA, biasA, tok0, initA);
+            }
+            pendB = true;
+            pendB_tok = tok0;
+        } else {
+            mul_fin(FIN_NO, q, WB, IB, cB, accB, accA, 0.0f, 0.0f, nullptr, 0);
+        }
+    };
+
+    x_issue(0);
+    w_issue(0, tileA, haveA, WA0, IA0, cA0);
+    w_issue(0, tileB, haveB, WB0, IB0, cB0);
+    x_commit(0);
+    wait_global_loads();
+    __syncthreads();
+    for (int p = 0; p < total; p += 2) {
+        {
+            const bool nxt = p + 1 < total;
+            if (nxt) {
+                x_issue(p + 1);
+                if (reload || p + 1 < 2) {
+                    w_issue(p + 1, tileA, haveA, WA1, IA1, cA1);
+                    w_issue(p + 1, tileB, haveB, WB1, IB1, cB1);
+                }
+            }
+            phase(p, WA0, IA0, cA0, WB0, IB0, cB0);
+            if (nxt) x_commit(p + 1);
+            wait_global_loads();
+            __syncthreads();
+        }
+        if (p + 1 >= total) break;
+        {
+            const bool nxt = p + 2 < total;
+            if (nxt) {
+                x_issue(p + 2);
+                if (reload) {
+                    w_issue(p + 2, tileA, haveA, WA0, IA0, cA0);
+                    w_issue(p + 2, tileB, haveB, WB0, IB0, cB0);
+                }
+            }
+            phase(p + 1, WA1, IA1, cA1, WB1, IB1, cB1);
             if (nxt) x_commit(p + 2);
             wait_global_loads();
             __syncthreads();
+        }
+    }
+    // the last token tile's B is still pending
+    if (pendB && storeB) {
+        if (a.out_vec_ok && pendB_tok + PIPE_TM <= a.M) {
+            uint8_t* o = out_ptr(nB, pendB_tok);
+#pragma unroll
+            for (int i = 0; i < PIPE_PIECES; ++i) finish_quad<OUT, POST>(a, accB[i], scaleB, biasB, o, i, lds);
+        } else {
+            finish_slow(accB, nB, scaleB, biasB, pendB_tok, initB);
         }
     }
 }
@@ -468,7 +797,8 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
 // ---------------------------------------------------------------------------------------
 bool plan_supported(int token_tile, int row_tiles_per_wave)
 {
-    if (token_tile == 128) return row_tiles_per_wave == 1 || row_tiles_per_wave == 8 || row_tiles_per_wave == 16;
+    if (token_tile == 128)
+        return row_tiles_per_wave == 1 || row_tiles_per_wave == 2 || row_tiles_per_wave == 8 || row_tiles_per_wave == 16;
     return (token_tile == 64) && (row_tiles_per_wave == 1 || row_tiles_per_wave == 2);
 }
 
@@ -483,8 +813,12 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
         p.waves = (p.max_steps == 4) ? 16 : 8;
         if (force_r == 8 || force_r == 16) p.waves = (force_r == 16 && p.max_steps != 4) ? 8 : force_r;
         p.row_tiles_per_wave = 1;
+        if (force_r == 2 && p.max_steps <= 6) {   // fused variant: 8 waves x 2 row tiles (else: hint ignored)
+            p.waves = FUSED_NW;
+            p.row_tiles_per_wave = 2;
+        }
         p.n_tok_tiles = (int)((M + PIPE_TM - 1) / PIPE_TM);
-        p.n_row_groups = (ntiles + p.waves - 1) / p.waves;
+        p.n_row_groups = (ntiles + p.waves * p.row_tiles_per_wave - 1) / (p.waves * p.row_tiles_per_wave);
         // one workgroup per CU: S token-tile streams per row group
         int S = num_cus / p.n_row_groups;
         if (S < 1) S = 1;
@@ -512,6 +846,15 @@ struct PipeLaunch {
     static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
     {
         hipLaunchKernelGGL((spmm_rowtile_mfma<NW, MAXS, OUT, POST>), grid, block, 0, st, a);
+    }
+};
+
+template <int MAXS>
+struct FusedLaunch {
+    template <int OUT, int POST>
+    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
+    {
+        hipLaunchKernelGGL((spmm_rowtile_mfma_fused<MAXS, OUT, POST>), grid, block, 0, st, a);
     }
 };
 
@@ -556,7 +899,10 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_posto
     const dim3 grid((unsigned)plan.workgroups), block((unsigned)plan.waves * 64);
     if (plan.token_tile == PIPE_TM) {
         if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
-        if (plan.waves == 16 && plan.max_steps == 4) dispatch_epilogue<PipeLaunch<16, 4>>(out_type, postop, grid, block, st, a);
+        if (plan.row_tiles_per_wave == 2 && plan.max_steps == 4) dispatch_epilogue<FusedLaunch<4>>(out_type, postop, grid, block, st, a);
+        else if (plan.row_tiles_per_wave == 2 && plan.max_steps == 6) dispatch_epilogue<FusedLaunch<6>>(out_type, postop, grid, block, st, a);
+        else if (plan.row_tiles_per_wave == 2) return (int)hipErrorInvalidValue;
+        else if (plan.waves == 16 && plan.max_steps == 4) dispatch_epilogue<PipeLaunch<16, 4>>(out_type, postop, grid, block, st, a);
         else if (plan.waves == 8 && plan.max_steps == 4) dispatch_epilogue<PipeLaunch<8, 4>>(out_type, postop, grid, block, st, a);
         else if (plan.waves == 8 && plan.max_steps == 6) dispatch_epilogue<PipeLaunch<8, 6>>(out_type, postop, grid, block, st, a);
         else if (plan.waves == 8 && plan.max_steps == 8) dispatch_epilogue<PipeLaunch<8, 8>>(out_type, postop, grid, block, st, a);

@@ -126,9 +126,9 @@ def test_config4_large_all_kernel_variants_agree_bitwise():
     case = wl.large_cases()[0]
     d = wl.make(case)
     a, _ = gpu_spmm(d["W"], d["X"], d, case)
-    b, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=(64, 1))
-    c, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=(64, 2))
-    assert np.array_equal(a, b) and np.array_equal(a, c)
+    for tuning in ((64, 1), (64, 2), (128, 1), (128, 2), (128, 8)):
+        b, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=tuning)
+        assert np.array_equal(a, b), tuning
 
 
 # ---------------------------------------------------------------------------- config 5 (sample of the grid)
@@ -152,7 +152,7 @@ def test_config5_grid_sample_s32_and_s8(case):
     (260, 100, 257), (5, 3000, 7),
 ])
 @pytest.mark.parametrize("out_type", ["s32", "s8"])
-@pytest.mark.parametrize("tuning", [None, (64, 2)], ids=["pipelined", "simple"])
+@pytest.mark.parametrize("tuning", [None, (128, 1), (128, 2), (64, 2)], ids=["default", "pipelined", "fused", "simple"])
 def test_ragged_shapes(N, K, M, out_type, tuning):
     case = wl.Case("ragged", N, K, M, 0.6, wl.N4K1, out_type, "none", keys=(60, N, K, M))
     check_case(case, tuning=tuning)
@@ -165,7 +165,10 @@ def test_many_token_tiles_and_segments(N, K, M, s):
     """Several token tiles per workgroup stream, 1 / 2 / 3+ K segments (resident and
     re-streamed weights), ragged last tile, every step-count variant of the kernel."""
     for ot, po in (("s32", "none"), ("s8", "gelu")):
-        check_case(wl.Case("multi", N, K, M, s, wl.N4K1, ot, po, keys=(66, N, K, M)))
+        for tuning in (None, (128, 1), (128, 2)):
+            if tuning == (128, 2) and s < 0.75:
+                continue   # the fused variant covers up to 6 steps per segment
+            check_case(wl.Case("multi", N, K, M, s, wl.N4K1, ot, po, keys=(66, N, K, M)), tuning=tuning)
 
 
 @pytest.mark.parametrize("out_type,postop", [("s32", "none"), ("f32", "none"), ("f32", "gelu"),
