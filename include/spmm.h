@@ -155,13 +155,17 @@ spmm_status_t spmm_make_gelu_lut(float mid_scale, float out_scale, int32_t out_z
 spmm_status_t spmm_plan(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
                         int32_t *token_tile, int32_t *rows_per_workgroup, int64_t *workgroups);
 
-/* Override the automatic choice for later spmm_run calls on this handle (0 = automatic).
- * token_tile 128 selects the pipelined kernels (row_tiles_per_wave 1, 8 or 16 = waves per
- * workgroup, 2 = fused variant; a variant that cannot hold the weight's densest segment falls
- * back to the automatic one), token_tile 64 the simple kernel (1 or 2 row tiles per wave).
- * Unsupported values return SPMM_E_UNSUPPORTED and change nothing.  Not thread-safe
- * against concurrent spmm_run on the same handle. */
-spmm_status_t spmm_set_tuning(spmm_handle_t *h, int32_t token_tile, int32_t row_tiles_per_wave);
+/* Override the automatic choice of kernel configuration for later spmm_run calls on this
+ * handle; (0, 0) restores the automatic choice.
+ *   token_tile 128: pipelined kernel, one workgroup per CU; variant 0 = automatic, 8 or 16 =
+ *                   waves per workgroup (16 only holds weights with <= 4 steps per segment,
+ *                   denser weights silently use 8).
+ *   token_tile  64: variant 0 or 8 = pipelined kernel with two workgroups per CU;
+ *                   variant 101 / 102 = the simple, unpipelined kernel with 1 / 2 row tiles
+ *                   per wave (an independent second implementation for cross-checks).
+ * Unsupported values return SPMM_E_UNSUPPORTED and change nothing.  Not thread-safe against
+ * concurrent spmm_run on the same handle. */
+spmm_status_t spmm_set_tuning(spmm_handle_t *h, int32_t token_tile, int32_t variant);
 
 /* Name of the device kernel spmm_run launches for this configuration (for profilers). */
 const char *spmm_kernel_name(void);

@@ -188,8 +188,8 @@ def spmm_plan(handle: int, M: int, out_type="s32") -> Tuple[int, int, int]:
     return int(a.value), int(b.value), int(c.value)
 
 
-def spmm_set_tuning(handle: int, token_tile: int = 0, row_tiles_per_wave: int = 0) -> None:
-    _check(lib().spmm_set_tuning(handle, int(token_tile), int(row_tiles_per_wave)), "spmm_set_tuning")
+def spmm_set_tuning(handle: int, token_tile: int = 0, variant: int = 0) -> None:
+    _check(lib().spmm_set_tuning(handle, int(token_tile), int(variant)), "spmm_set_tuning")
 
 
 def make_epilogue(w_scale=None, x_scale: float = 1.0, x_zero_point: int = 0, bias=None, postop="none",

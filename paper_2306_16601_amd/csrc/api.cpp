@@ -171,14 +171,13 @@ spmm_status_t spmm_plan(const spmm_handle_t* h, int64_t M, spmm_out_t out_type, 
     return SPMM_OK;
 }
 
-spmm_status_t spmm_set_tuning(spmm_handle_t* h, int32_t token_tile, int32_t row_tiles_per_wave)
+spmm_status_t spmm_set_tuning(spmm_handle_t* h, int32_t token_tile, int32_t variant)
 {
-    if (!h || token_tile < 0 || row_tiles_per_wave < 0) return SPMM_E_ARG;
-    const int tm = token_tile ? token_tile : 128;
-    const int r = row_tiles_per_wave ? row_tiles_per_wave : 1;
-    if (!spmm::plan_supported(tm, r)) return SPMM_E_UNSUPPORTED;
+    if (!h || token_tile < 0 || variant < 0) return SPMM_E_ARG;
+    if (token_tile == 0 && variant != 0) return SPMM_E_ARG;
+    if (token_tile != 0 && !spmm::plan_supported(token_tile, variant)) return SPMM_E_UNSUPPORTED;
     h->force_tm = token_tile;
-    h->force_r = row_tiles_per_wave;
+    h->force_r = variant;
     return SPMM_OK;
 }
 

@@ -84,16 +84,19 @@ struct KernelArgs {
 };
 
 struct Plan {
-    int token_tile;          // TM: 128 = pipelined persistent kernel, 64 = simple kernel
-    int row_tiles_per_wave;  // R (simple kernel only)
+    int token_tile;          // TM of the pipelined kernel (128: one workgroup per CU, 64: two), or 64 for the simple kernel
+    int row_tiles_per_wave;  // 1 (pipelined) or 1 / 2 (simple kernel)
     int waves;               // NW
+    int simple;              // 1: simple kernel
     int max_steps;           // unroll bound of the per-segment step loop (pipelined kernel)
     int n_row_groups, n_tok_tiles, n_streams, xcd_map;
     int64_t workgroups;
 };
 
-bool plan_supported(int token_tile, int row_tiles_per_wave);
-Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int force_r);
+// variant: 0 = automatic, 8 / 16 = waves per workgroup (pipelined), 101 / 102 = simple kernel
+// with 1 / 2 row tiles per wave (token tile 64 only)
+bool plan_supported(int token_tile, int variant);
+Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant);
 // Launches the SpMM kernel; returns a hipError_t value as int (0 = success).
 int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_postop_t postop, void* stream);
 

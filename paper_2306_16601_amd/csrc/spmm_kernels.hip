@@ -34,7 +34,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
-#include <type_traits>
 
 #include "spmm_internal.h"
 
@@ -54,11 +53,32 @@ __device__ __forceinline__ float gelu_f32(float y)
     return (float)(0.5 * x * erfc(-x * 0.70710678118654752440));
 }
 
-// Post-operators for 4 consecutive tokens m0..m0+3 of output row n.  `lut` is the table of
-// Algorithm 2 (any address space; LDS in the pipelined kernel).
-template <int OUT, int POST, typename LutPtr>
+// Where the table of Algorithm 2 is read from.
+struct GlobalLut {
+    const int8_t* p;
+    __device__ __forceinline__ uint32_t operator()(uint32_t key) const { return (uint8_t)p[key]; }
+};
+
+// quantised code of one pre-activation y (Quantize post-operator / table look-up)
+template <int OUT, int POST, typename Lut>
+__device__ __forceinline__ uint32_t quantise(const KernelArgs& a, const float y, const Lut& lut)
+{
+    if constexpr (POST == SPMM_POST_GELU) {
+        // key = sat_s8(rint(y / mid_scale)) + 128; v_cvt_pk_u8_f32 converts with saturation to [0, 255]
+        const float t = rintf(y * a.inv_mid) + 128.0f;
+        return lut(__builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u));
+    } else {
+        const float lo = (OUT == SPMM_OUT_U8) ? 0.0f : -128.0f;
+        const float hi = (OUT == SPMM_OUT_U8) ? 255.0f : 127.0f;
+        return (uint32_t)((int)fminf(hi, fmaxf(lo, rintf(y * a.inv_out) + a.out_zp_f))) & 0xffu;
+    }
+}
+
+// Generic post-operators + store for 4 consecutive tokens m0..m0+3 of output row n: any
+// alignment, any tail (the slow path of every kernel).
+template <int OUT, int POST, typename Lut>
 __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, const float s, const float b,
-                                        const int n, const int m0, LutPtr lut)
+                                        const int n, const int m0, const Lut& lut)
 {
     const int valid = a.M - m0;   // > 0 guaranteed by caller
     if constexpr (OUT == SPMM_OUT_S32) {
@@ -88,24 +108,8 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
             }
         } else {
             uint32_t q[4];
-            if constexpr (POST == SPMM_POST_GELU) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    // key = sat_s8(rint(y / mid_scale)); looked up as key + 128 in [0, 255]
-                    // (v_cvt_pk_u8_f32 converts with saturation to [0, 255])
-                    const float t = rintf(y[r] * a.inv_mid) + 128.0f;
-                    const uint32_t key = __builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u);
-                    q[r] = (uint32_t)(uint8_t)lut[key];
-                }
-            } else {
-                const float lo = (OUT == SPMM_OUT_U8) ? 0.0f : -128.0f;
-                const float hi = (OUT == SPMM_OUT_U8) ? 255.0f : 127.0f;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float t = fminf(hi, fmaxf(lo, rintf(y[r] * a.inv_out) + a.out_zp_f));
-                    q[r] = (uint32_t)((int)t) & 0xffu;
-                }
-            }
+            for (int r = 0; r < 4; ++r) q[r] = quantise<OUT, POST>(a, y[r], lut);
             uint8_t* o = (uint8_t*)a.out + (int64_t)n * a.ldo + m0;
             if (a.out_vec_ok && valid >= 4) {
                 *(uint32_t*)o = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
@@ -117,10 +121,10 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
     }
 }
 
-// s_waitcnt vmcnt(0) only (expcnt / lgkmcnt fields left at their maxima).  Issued at the end
-// of a phase, when the prefetches started at its beginning have long landed: it tells the
-// compiler's wait-count bookkeeping that no global load is outstanding, so the next phase's
-// multiply loop does not stall on the prefetches issued just before it.
+// s_waitcnt vmcnt(0) only (expcnt / lgkmcnt fields left at their maxima).  Issued when the
+// prefetches started at the beginning of a phase have long landed: it tells the compiler's
+// wait-count bookkeeping that no global load is outstanding, so the next phase's multiply
+// loop does not stall on the prefetches issued just before it.
 __device__ __forceinline__ void wait_global_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // 16 bytes of activation row `krow` starting at token `col`; tokens >= M read as 0.
@@ -136,41 +140,72 @@ __device__ __forceinline__ v4i load_x16(const KernelArgs& a, const int krow, con
 }
 
 // =======================================================================================
-// Pipelined persistent kernel (the one spmm_run launches by default).
+// Pipelined persistent kernel (the one spmm_run launches).
 //
-// Workgroup = NW waves (16 or 8), one workgroup per CU.  Wave w owns row tile NW*rg + w (16 output rows) for the
-// whole kernel; the workgroup walks over token tiles of 128 tokens (stream, stream + S, ..)
-// and, inside a token tile, over the K segments of 512 rows.  One (token tile, segment)
-// pair is a "phase".  LDS holds two activation buffers [512 rows][128 + 16 bytes]; while
-// phase p multiplies out of buffer p % 2, the global loads for phase p+1 are in flight in
-// registers and are written to the other buffer afterwards; one barrier per phase.
-// The compressed weights of a phase (at most MAXS steps of 64 listed k) live in one of two
-// register sets; with at most two segments they are loaded once per workgroup and reused
-// for every token tile, otherwise they are prefetched one phase ahead.
+// Workgroup = NW waves.  Wave w owns row tile NW*rg + w (16 output rows) for the whole
+// kernel; the workgroup walks over token tiles of TM tokens (stream, stream + S, ..) and,
+// inside a token tile, over the K segments of 512 rows.  One (token tile, segment) pair is a
+// "phase".  LDS holds two activation buffers [512 rows][TM + 16 bytes]; while phase p
+// multiplies out of buffer p % 2, the global loads for phase p+1 are in flight in registers
+// and are written to the other buffer afterwards; one barrier per phase.  The compressed
+// weights of a phase (at most MAXS steps of 64 listed k) live in one of two register sets;
+// with at most two segments they are loaded once per workgroup and reused for every token
+// tile, otherwise they are prefetched one phase ahead.
+//
+// Two LDS geometries:
+//   TM = 128: 16 (or 8) waves, one workgroup per CU; table at LDS offset 0, buffers behind.
+//   TM =  64: 8 waves and 80 KB, so that TWO workgroups share a CU: while one is in its
+//             VALU-bound post-operators or waits at a barrier, the other one keeps the LDS
+//             and the matrix cores busy.
+// Every LDS row has 16 spare bytes behind its TM tokens (the pitch TM + 16 makes consecutive
+// rows start 4 banks apart).  These spare chunks carry the output staging for 1-byte outputs
+// (and, for TM = 64 where no LDS is left, the table): wave w transposes its 16 rows x 64
+// tokens through chunks 64w .. 64w+63 so that a row's tokens leave in 64-byte runs instead
+// of 4-byte pieces.  Staging row r, 16-token piece j lives in chunk 4r + (j ^ (r >> 2)): with
+// both pitches the 4-byte writes and the 16-byte reads then touch every LDS bank once.
 // =======================================================================================
-constexpr int PIPE_TM = 128;
-constexpr int PIPE_STRIDE = PIPE_TM + 16;                   // 144 B: consecutive rows start 4 banks apart
-constexpr int PIPE_BUF_BYTES = SEGMENT_ROWS * PIPE_STRIDE;  // 73728 B
-constexpr int PIPE_PIECES = PIPE_TM / 16;                   // 8 MFMA token sub-tiles
-constexpr int PIPE_LUT = 0;                                 // table of Algorithm 2 at LDS offset 0: the key is the address
-constexpr int PIPE_X0 = 256;                                // activation buffers behind it (two, back to back)
-constexpr int PIPE_LDS = PIPE_X0 + 2 * PIPE_BUF_BYTES;
-// Output staging for 1-byte outputs.  Every LDS row has 16 spare bytes behind its 128 tokens
-// (1024 such chunks over both buffers); wave w transposes its 16 rows x 64 tokens through
-// chunks 64w .. 64w+63 so that a row's tokens leave in 64-byte runs instead of 4-byte pieces.
-// Staging row r, 16-token piece j lives in chunk 4r + (j ^ (r >> 2)): with the 144-byte pitch
-// both the 4-byte writes and the 16-byte reads then touch every LDS bank exactly once.
-constexpr int PIPE_PAD0 = PIPE_X0 + PIPE_TM;
+template <int TM>
+struct Geo;
+
+template <>
+struct Geo<128> {
+    static constexpr int STRIDE = 144, PIECES = 8, HALVES = 2;
+    static constexpr int BUF = SEGMENT_ROWS * STRIDE;   // 73728
+    static constexpr int X0 = 256;                      // table in [0, 256): the key is the address
+    static constexpr int LDS = X0 + 2 * BUF;
+    static __device__ __forceinline__ uint32_t lut_addr(uint32_t key) { return key; }
+    // spare chunk n in [0, 1024): behind row n of the two back-to-back buffers
+    static __device__ __forceinline__ uint32_t chunk(uint32_t n) { return X0 + n * STRIDE + 128; }
+};
+
+template <>
+struct Geo<64> {
+    static constexpr int STRIDE = 80, PIECES = 4, HALVES = 1;
+    static constexpr int BUF = SEGMENT_ROWS * STRIDE;   // 40960
+    static constexpr int X0 = 0;
+    static constexpr int LDS = 2 * BUF;                 // 81920: two workgroups per CU
+    // table entry e in the spare chunk of row e / 16 of buffer 0: 64 distinct banks for 64 dwords
+    static __device__ __forceinline__ uint32_t lut_addr(uint32_t key) { return key + (key >> 4) * 64 + 64; }
+    // staging chunk n in [0, 512): behind row n of buffer 1
+    static __device__ __forceinline__ uint32_t chunk(uint32_t n) { return BUF + n * STRIDE + 64; }
+};
+
+template <int TM>
+struct LdsLut {
+    const uint8_t* lds;
+    __device__ __forceinline__ uint32_t operator()(uint32_t key) const { return lds[Geo<TM>::lut_addr(key)]; }
+};
 
 // Post-operators + store for one full token tile of one wave, everything in bounds and
 // aligned: lane (g, c) holds tokens tok0 + 16 i + 4 g + {0..3} of output row 16 * tile + c.
 // 4-byte outputs are stored straight from the accumulator layout (16 bytes per lane, 64-byte
-// runs per row); 1-byte outputs go through the LDS staging chunks described above.
-template <int OUT, int POST>
-__device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i (&acc)[PIPE_PIECES], const float scale,
-                                                 const float bias, const int tile, const int tok0, int lane,
-                                                 const int wave, uint8_t* lds)
+// runs per row); 1-byte outputs go through the LDS staging chunks.
+template <int TM, int OUT, int POST>
+__device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i (&acc)[Geo<TM>::PIECES],
+                                                 const float scale, const float bias, const int tile,
+                                                 const int tok0, int lane, const int wave, uint8_t* lds)
 {
+    using G = Geo<TM>;
     // Keep the address arithmetic below local to the epilogue: without this the compiler hoists
     // it out of the phase loop and the long-lived results push the kernel into register spills.
     asm volatile("" : "+v"(lane));
@@ -179,13 +214,13 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
         int32_t* o = (int32_t*)a.out + ((int64_t)(tile * TILE_ROWS + c) * a.ldo + tok0 + 4 * g);
         if (tile * TILE_ROWS + c < a.N) {
 #pragma unroll
-            for (int i = 0; i < PIPE_PIECES; ++i) *(v4i*)(o + 16 * i) = acc[i];
+            for (int i = 0; i < G::PIECES; ++i) *(v4i*)(o + 16 * i) = acc[i];
         }
     } else if constexpr (OUT == SPMM_OUT_F32) {
         float* o = (float*)a.out + ((int64_t)(tile * TILE_ROWS + c) * a.ldo + tok0 + 4 * g);
         if (tile * TILE_ROWS + c < a.N) {
 #pragma unroll
-            for (int i = 0; i < PIPE_PIECES; ++i) {
+            for (int i = 0; i < G::PIECES; ++i) {
                 v4f y;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -196,36 +231,25 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
             }
         }
     } else {
+        const LdsLut<TM> lut{lds};
         // write side: this lane's quad of piece j goes to staging row c, piece j
-        const uint32_t wbase = PIPE_PAD0 + (uint32_t)(64 * wave + 4 * c) * PIPE_STRIDE + 4 * g;
+        const uint32_t wbase = G::chunk(64 * wave + 4 * c) + 4 * g;
         const int wsw = c >> 2;
         // read side: this lane fetches 16 tokens of staging row lane / 4, piece lane % 4
         const int rr = lane >> 2, rj = lane & 3;
-        const uint32_t raddr = PIPE_PAD0 + (uint32_t)(64 * wave + 4 * rr + (rj ^ (rr >> 2))) * PIPE_STRIDE;
+        const uint32_t raddr = G::chunk(64 * wave + 4 * rr + (rj ^ (rr >> 2)));
         const int orow = tile * TILE_ROWS + rr;
         uint8_t* o = (uint8_t*)a.out + ((int64_t)orow * a.ldo + tok0 + 16 * rj);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < G::HALVES; ++h) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = 4 * h + j;
                 uint32_t word = 0;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float y = __fmaf_rn((float)acc[i][r], scale, bias);
-                    uint32_t q;
-                    if constexpr (POST == SPMM_POST_GELU) {
-                        // key = sat_s8(rint(y / mid_scale)) + 128; v_cvt_pk_u8_f32 saturates to [0, 255]
-                        const float t = rintf(y * a.inv_mid) + 128.0f;
-                        q = lds[PIPE_LUT + __builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u)];
-                    } else {
-                        const float lo = (OUT == SPMM_OUT_U8) ? 0.0f : -128.0f;
-                        const float hi = (OUT == SPMM_OUT_U8) ? 255.0f : 127.0f;
-                        q = (uint32_t)((int)fminf(hi, fmaxf(lo, rintf(y * a.inv_out) + a.out_zp_f))) & 0xffu;
-                    }
-                    word |= q << (8 * r);
-                }
-                *(uint32_t*)(lds + wbase + (uint32_t)(j ^ wsw) * PIPE_STRIDE) = word;
+                for (int r = 0; r < 4; ++r)
+                    word |= quantise<OUT, POST>(a, __fmaf_rn((float)acc[i][r], scale, bias), lut) << (8 * r);
+                *(uint32_t*)(lds + wbase + (uint32_t)(j ^ wsw) * G::STRIDE) = word;
             }
             const v4i v = *(const v4i*)(lds + raddr);   // same wave: LDS operations complete in order
             if (orow < a.N) *(v4i*)(o + 64 * h) = v;
@@ -233,12 +257,16 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
     }
 }
 
-template <int NW, int MAXS, int OUT, int POST>
+template <int TM, int NW, int MAXS, int OUT, int POST>
 __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
 {
+    using G = Geo<TM>;
     constexpr int NTHREADS = NW * 64;
-    constexpr int XLOADS = SEGMENT_ROWS * PIPE_PIECES / NTHREADS;   // 16-byte loads per thread and phase
-    __shared__ __attribute__((aligned(16))) uint8_t lds[PIPE_LDS];
+    constexpr int PIECES = G::PIECES;
+    constexpr int ROWS_PER_PASS = NTHREADS / PIECES;                // activation rows one load pass covers
+    constexpr int XLOADS = SEGMENT_ROWS / ROWS_PER_PASS;            // 16-byte loads per thread and phase
+    static_assert(XLOADS * ROWS_PER_PASS == SEGMENT_ROWS, "threads must tile a segment");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[G::LDS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -275,50 +303,50 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         }
     }
     if constexpr (POST == SPMM_POST_GELU && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8)) {
-        if (tid < 256) lds[PIPE_LUT + tid] = (uint8_t)a.lut[tid];
+        if (tid < 256) lds[G::lut_addr(tid)] = (uint8_t)a.lut[tid];
     }
 
     v4i A0[MAXS], A1[MAXS];
     uint32_t I0[MAXS], I1[MAXS];
     int n0 = 0, n1 = 0;
     v4i xr[XLOADS];
-    v4i acc[PIPE_PIECES];
+    v4i acc[PIECES];
 #pragma unroll
-    for (int i = 0; i < PIPE_PIECES; ++i) acc[i] = (v4i){init, init, init, init};
+    for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
 
-    // per-thread staging coordinates: XLOADS rows (NTHREADS / 8 apart), one 16-byte piece
-    const int x_row0 = tid >> 3, x_piece = tid & 7;
-    const uint32_t x_lds0 = PIPE_X0 + (uint32_t)x_row0 * PIPE_STRIDE + x_piece * 16;
+    // per-thread staging coordinates: XLOADS rows (ROWS_PER_PASS apart), one 16-byte piece
+    const int x_row0 = tid / PIECES, x_piece = tid % PIECES;
+    const uint32_t x_lds0 = G::X0 + (uint32_t)x_row0 * G::STRIDE + x_piece * 16;
 
     // ---- global loads of the activations of phase q into registers.  The common case (16-byte
     // aligned rows, full token tile) is branch-free so that all loads are in flight together;
     // rows past the end of K are redirected to the last valid row (never multiplied).
     auto x_issue = [&](const int q) {
         const int j = q / a.nseg, seg = q - j * a.nseg;
-        const int tok0 = (stream + j * S) * PIPE_TM;
+        const int tok0 = (stream + j * S) * TM;
         const int k0 = seg * SEGMENT_ROWS;
         const int last = min(SEGMENT_ROWS, a.K - k0) - 1;
-        if (a.x_vec_ok && tok0 + PIPE_TM <= a.M) {
+        if (a.x_vec_ok && tok0 + TM <= a.M) {
             const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0 + x_piece * 16;
 #pragma unroll
             for (int u = 0; u < XLOADS; ++u) {
-                const int row = min(x_row0 + u * (NTHREADS / 8), last);
+                const int row = min(x_row0 + u * ROWS_PER_PASS, last);
                 xr[u] = *(const v4i*)(src + (int64_t)row * a.ldx);
             }
         } else {
 #pragma unroll
             for (int u = 0; u < XLOADS; ++u) {
-                const int row = min(x_row0 + u * (NTHREADS / 8), last);
+                const int row = min(x_row0 + u * ROWS_PER_PASS, last);
                 xr[u] = load_x16(a, k0 + row, tok0 + x_piece * 16);
             }
         }
     };
     // ---- ... and from registers into LDS buffer q % 2, as x - 128
     auto x_commit = [&](const int q) {
-        uint8_t* buf = lds + (q & 1) * PIPE_BUF_BYTES + x_lds0;
+        uint8_t* buf = lds + (q & 1) * G::BUF + x_lds0;
 #pragma unroll
         for (int u = 0; u < XLOADS; ++u)
-            *(v4i*)(buf + u * (NTHREADS / 8) * PIPE_STRIDE) = xr[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+            *(v4i*)(buf + u * ROWS_PER_PASS * G::STRIDE) = xr[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
     };
     // ---- compressed weights + activation-row indices of (tile, segment of phase q).  Loads are
     // unconditional (slots past the segment's step count re-read step 0 and are never used).
@@ -337,17 +365,17 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
             I[s] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
         }
     };
-    // ---- multiply phase q: gather + transpose out of LDS, 8 matrix instructions per step
+    // ---- multiply phase q: gather + transpose out of LDS, PIECES matrix instructions per step
     auto multiply = [&](const int q, const v4i (&A)[MAXS], const uint32_t (&I)[MAXS], const int cnt) {
-        const uint32_t base = PIPE_X0 + (uint32_t)(q & 1) * PIPE_BUF_BYTES + (c & 1) * 8;
+        const uint32_t base = G::X0 + (uint32_t)(q & 1) * G::BUF + (c & 1) * 8;
 #pragma unroll
         for (int s = 0; s < MAXS; ++s) {
             if (s < cnt) {
                 // this lane supplies the address of list slot 16g + c/2 (and + 8), token half c & 1
-                const uint32_t a0 = (I[s] & 0xffffu) * PIPE_STRIDE + base;
-                const uint32_t a1 = (I[s] >> 16) * PIPE_STRIDE + base;
+                const uint32_t a0 = (I[s] & 0xffffu) * G::STRIDE + base;
+                const uint32_t a1 = (I[s] >> 16) * G::STRIDE + base;
 #pragma unroll
-                for (int i = 0; i < PIPE_PIECES; ++i) {
+                for (int i = 0; i < PIECES; ++i) {
                     const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0 + 16 * i));
                     const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1 + 16 * i));
                     const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
@@ -360,20 +388,21 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     auto finish = [&](const int q) {
         const int j = q / a.nseg;
         if (q - j * a.nseg != a.nseg - 1) return;
-        const int tok0 = (stream + j * S) * PIPE_TM;
+        const int tok0 = (stream + j * S) * TM;
         if (have_tile) {
-            if (a.out_vec_ok && tok0 + PIPE_TM <= a.M) {
-                finish_tile_fast<OUT, POST>(a, acc, scale, bias, tile, tok0, lane, wave, lds);
+            if (a.out_vec_ok && tok0 + TM <= a.M) {
+                finish_tile_fast<TM, OUT, POST>(a, acc, scale, bias, tile, tok0, lane, wave, lds);
             } else if (n < a.N) {
+                const LdsLut<TM> lut{lds};
 #pragma unroll
-                for (int i = 0; i < PIPE_PIECES; ++i) {
+                for (int i = 0; i < PIECES; ++i) {
                     const int m0 = tok0 + 16 * i + 4 * g;
-                    if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, lds + PIPE_LUT);
+                    if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, lut);
                 }
             }
         }
 #pragma unroll
-        for (int i = 0; i < PIPE_PIECES; ++i) acc[i] = (v4i){init, init, init, init};
+        for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
     };
     const bool reload = a.nseg > 2;   // otherwise set q % 2 always holds segment q % nseg
 
@@ -412,305 +441,10 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
 }
 
 // =======================================================================================
-// Fused variant: 8 waves per workgroup, two row tiles (A, B) per wave, post-operators of one
-// tile interleaved with the matrix instructions of the other.
-//
-// The post-operator chain is pure VALU work (about 8 instructions per output) while the
-// multiply is LDS + matrix-core work; run one after the other they leave each unit idle
-// half of the time.  Here every phase is  [multiply A | finish B of the previous token
-// tile]  then  [multiply B | finish A if this was the last segment], written as one
-// instruction stream per wave so that the VALU slices fill the shadow of the matrix
-// instructions and of the LDS latency.  Same LDS layout and phase pipeline as above.
-// =======================================================================================
-constexpr int FUSED_NW = 8;
-constexpr int FUSED_LUT = PIPE_LUT;
-constexpr int FUSED_X0 = PIPE_X0;
-
-// post-operators for 4 consecutive tokens (one accumulator quad) in the aligned fast path
-template <int OUT, int POST>
-__device__ __forceinline__ void finish_quad(const KernelArgs& a, const v4i acc, const float scale, const float bias,
-                                            uint8_t* optr, const int piece, const uint8_t* lds)
-{
-    if constexpr (OUT == SPMM_OUT_S32) {
-        *(v4i*)((int32_t*)optr + 16 * piece) = acc;
-    } else if constexpr (OUT == SPMM_OUT_F32) {
-        v4f y;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            y[r] = __fmaf_rn((float)acc[r], scale, bias);
-            if constexpr (POST == SPMM_POST_GELU) y[r] = gelu_f32(y[r]);
-        }
-        *(v4f*)((float*)optr + 16 * piece) = y;
-    } else {
-        uint32_t word = 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float y = __fmaf_rn((float)acc[r], scale, bias);
-            uint32_t q;
-            if constexpr (POST == SPMM_POST_GELU) {
-                const float t = rintf(y * a.inv_mid) + 128.0f;
-                q = lds[FUSED_LUT + __builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u)];
-            } else {
-                const float lo = (OUT == SPMM_OUT_U8) ? 0.0f : -128.0f;
-                const float hi = (OUT == SPMM_OUT_U8) ? 255.0f : 127.0f;
-                q = (uint32_t)((int)fminf(hi, fmaxf(lo, rintf(y * a.inv_out) + a.out_zp_f))) & 0xffu;
-            }
-            word |= q << (8 * r);
-        }
-        *(uint32_t*)(optr + 16 * piece) = word;
-    }
-}
-
-template <int MAXS, int OUT, int POST>
-__global__ void __launch_bounds__(FUSED_NW * 64) spmm_rowtile_mfma_fused(const KernelArgs a)
-{
-    constexpr int NTHREADS = FUSED_NW * 64;
-    constexpr int XLOADS = SEGMENT_ROWS * PIPE_PIECES / NTHREADS;   // 8
-    constexpr int ESZ = (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8) ? 1 : 4;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[FUSED_X0 + 2 * PIPE_BUF_BYTES];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g = lane >> 4, c = lane & 15;
-
-    int rg, stream;
-    {
-        const int b = blockIdx.x;
-        if (a.xcd_map) {
-            const int local = b >> 3;
-            stream = (b & 7) + 8 * (local / a.n_row_groups);
-            rg = local % a.n_row_groups;
-        } else {
-            rg = b % a.n_row_groups;
-            stream = b / a.n_row_groups;
-        }
-    }
-    const int S = a.n_streams;
-    const int n_my = (a.n_tok_tiles - stream + S - 1) / S;
-    const int total = n_my * a.nseg;
-
-    // the wave's two row tiles
-    const int tileA = (rg * FUSED_NW + wave) * 2, tileB = tileA + 1;
-    const bool haveA = tileA < a.ntiles, haveB = tileB < a.ntiles;
-    const int nA = tileA * TILE_ROWS + c, nB = tileB * TILE_ROWS + c;
-    const int initA = haveA ? a.rowsum[nA] * a.corr_mul : 0;
-    const int initB = haveB ? a.rowsum[nB] * a.corr_mul : 0;
-    float scaleA = 0.0f, biasA = 0.0f, scaleB = 0.0f, biasB = 0.0f;
-    if constexpr (OUT != SPMM_OUT_S32) {
-        if (haveA && nA < a.N) { scaleA = a.w_scale[nA] * a.x_scale; if (a.bias) biasA = a.bias[nA]; }
-        if (haveB && nB < a.N) { scaleB = a.w_scale[nB] * a.x_scale; if (a.bias) biasB = a.bias[nB]; }
-    }
-    if constexpr (POST == SPMM_POST_GELU && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8)) {
-        if (tid < 256) lds[FUSED_LUT + tid] = (uint8_t)a.lut[tid];
-    }
-    const bool storeA = haveA && nA < a.N, storeB = haveB && nB < a.N;
-
-    v4i WA0[MAXS], WA1[MAXS], WB0[MAXS], WB1[MAXS];
-    uint32_t IA0[MAXS], IA1[MAXS], IB0[MAXS], IB1[MAXS];
-    int cA0 = 0, cA1 = 0, cB0 = 0, cB1 = 0;
-    v4i xr[XLOADS];
-    v4i accA[PIPE_PIECES], accB[PIPE_PIECES];
-#pragma unroll
-    for (int i = 0; i < PIPE_PIECES; ++i) {
-        accA[i] = (v4i){initA, initA, initA, initA};
-        accB[i] = (v4i){initB, initB, initB, initB};
-    }
-
-    const int x_row0 = tid >> 3, x_piece = tid & 7;
-    const uint32_t x_lds0 = FUSED_X0 + (uint32_t)x_row0 * PIPE_STRIDE + x_piece * 16;
-
-    auto tok_of = [&](const int q) { return (stream + (q / a.nseg) * S) * PIPE_TM; };
-    auto x_issue = [&](const int q) {
-        const int j = q / a.nseg, seg = q - j * a.nseg;
-        const int tok0 = (stream + j * S) * PIPE_TM;
-        const int k0 = seg * SEGMENT_ROWS;
-        const int last = min(SEGMENT_ROWS, a.K - k0) - 1;
-        if (a.x_vec_ok && tok0 + PIPE_TM <= a.M) {
-            const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0 + x_piece * 16;
-#pragma unroll
-            for (int u = 0; u < XLOADS; ++u) {
-                const int row = min(x_row0 + u * (NTHREADS / 8), last);
-                xr[u] = *(const v4i*)(src + (int64_t)row * a.ldx);
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < XLOADS; ++u) {
-                const int row = min(x_row0 + u * (NTHREADS / 8), last);
-                xr[u] = load_x16(a, k0 + row, tok0 + x_piece * 16);
-            }
-        }
-    };
-    auto x_commit = [&](const int q) {
-        uint8_t* buf = lds + (q & 1) * PIPE_BUF_BYTES + x_lds0;
-#pragma unroll
-        for (int u = 0; u < XLOADS; ++u)
-            *(v4i*)(buf + u * (NTHREADS / 8) * PIPE_STRIDE) = xr[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
-    };
-    auto w_issue = [&](const int q, const int tile, const bool have, v4i (&W)[MAXS], uint32_t (&I)[MAXS], int& cnt) {
-        cnt = 0;
-        int s0 = 0;
-        if (have) {
-            const int seg = q % a.nseg;
-            s0 = a.seg_ptr[tile * a.nseg + seg];
-            cnt = a.seg_ptr[tile * a.nseg + seg + 1] - s0;
-        }
-#pragma unroll
-        for (int s = 0; s < MAXS; ++s) {
-            const int step = (s < cnt) ? s0 + s : 0;
-            W[s] = *(const v4i*)(a.vals + (int64_t)step * STEP_VAL_BYTES + lane * 16);
-            I[s] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
-        }
-    };
-    // multiply one tile for phase q; if FIN, finish the 8 accumulator quads of `fin` on the way
-    // (one quad after every third matrix instruction; quads of skipped steps run in their place)
-    auto mul_fin = [&](auto fin_tag, const int q, const v4i (&W)[MAXS], const uint32_t (&I)[MAXS], const int cnt,
-                       v4i (&acc)[PIPE_PIECES], v4i (&fin)[PIPE_PIECES], const float fscale, const float fbias,
-                       uint8_t* foptr, const int finit) {
-        constexpr bool FIN = decltype(fin_tag)::value;
-        const uint32_t base = FUSED_X0 + (uint32_t)(q & 1) * PIPE_BUF_BYTES + (c & 1) * 8;
-#pragma unroll
-        for (int s = 0; s < MAXS; ++s) {
-            if (s < cnt) {
-                const uint32_t a0 = (I[s] & 0xffffu) * PIPE_STRIDE + base;
-                const uint32_t a1 = (I[s] >> 16) * PIPE_STRIDE + base;
-#pragma unroll
-                for (int i = 0; i < PIPE_PIECES; ++i) {
-                    const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0 + 16 * i));
-                    const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1 + 16 * i));
-                    const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
-                    acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, W[s], acc[i], 0, 0, 0);
-                    if constexpr (FIN) {
-                        constexpr int dummy = 0; (void)dummy;
-                        const int m = 8 * s + i;
-                        if (m % 3 == 2 && m / 3 < PIPE_PIECES) {
-                            finish_quad<OUT, POST>(a, fin[m / 3], fscale, fbias, foptr, m / 3, lds);
-                            fin[m / 3] = (v4i){finit, finit, finit, finit};
-                        }
-                    }
-                }
-            } else if constexpr (FIN) {
-#pragma unroll
-                for (int i = 0; i < PIPE_PIECES; ++i) {
-                    const int m = 8 * s + i;
-                    if (m % 3 == 2 && m / 3 < PIPE_PIECES) {
-                        finish_quad<OUT, POST>(a, fin[m / 3], fscale, fbias, foptr, m / 3, lds);
-                        fin[m / 3] = (v4i){finit, finit, finit, finit};
-                    }
-                }
-            }
-        }
-        static_assert(8 * MAXS / 3 >= PIPE_PIECES, "all quads must be scheduled inside the step loop");
-    };
-    // generic (ragged / unaligned) finish of a whole tile, not overlapped
-    auto finish_slow = [&](v4i (&acc)[PIPE_PIECES], const int n, const float scale, const float bias, const int tok0,
-                           const int init) {
-#pragma unroll
-        for (int i = 0; i < PIPE_PIECES; ++i) {
-            const int m0 = tok0 + 16 * i + 4 * g;
-            if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, lds + FUSED_LUT);
-            acc[i] = (v4i){init, init, init, init};
-        }
-    };
-    auto out_ptr = [&](const int n, const int tok0) {
-        return (uint8_t*)a.out + ((int64_t)n * a.ldo + tok0 + 4 * g) * ESZ;
-    };
-    std::true_type FIN_YES;
-    std::false_type FIN_NO;
-
-    const bool reload = a.nseg > 2;
-    // pendB: tile B of token offset pendB_tok still has to be finished (during the next multiply of A)
-    bool pendB = false;
-    int pendB_tok = 0;
-
-    // one phase with register sets (WA, IA, cA) / (WB, IB, cB)
-    auto phase = [&](const int q, const v4i (&WA)[MAXS], const uint32_t (&IA)[MAXS], const int cA,
-                     const v4i (&WB)[MAXS], const uint32_t (&IB)[MAXS], const int cB) {
-        const int j = q / a.nseg;
-        const bool last_seg = (q - j * a.nseg == a.nseg - 1);
-        const int tok0 = (stream + j * S) * PIPE_TM;
-        // ---- part 1: multiply A, finishing B of the previous token tile on the way
-        if (pendB) {
-            const bool fast = a.out_vec_ok && pendB_tok + PIPE_TM <= a.M;
-            if (storeB && fast) {
-                mul_fin(FIN_YES, q, WA, IA, cA, accA, accB, scaleB, biasB, out_ptr(nB, pendB_tok), initB);
-            } else {
-                if (storeB) finish_slow(accB, nB, scaleB, biasB, pendB_tok, initB);
-                mul_fin(FIN_NO, q, WA, IA, cA, accA, accB, 0.0f, 0.0f, nullptr, 0);
-            }
-            pendB = false;
-        } else {
-            mul_fin(FIN_NO, q, WA, IA, cA, accA, accB, 0.0f, 0.0f, nullptr, 0);
-        }
-        // ---- part 2: multiply B, finishing A if this was the last segment
-        if (last_seg) {
-            const bool fast = a.out_vec_ok && tok0 + PIPE_TM <= a.M;
-            if (storeA && fast) {
-                mul_fin(FIN_YES, q, WB, IB, cB, accB, accA, scaleA, biasA, out_ptr(nA, tok0), initA);
-            } else {
-                mul_fin(FIN_NO, q, WB, IB, cB, accB, accA, 0.0f, 0.0f, nullptr, 0);
-                if (storeA) finish_slow(accA, nA, scaleA, biasA, tok0, initA);
-            }
-            pendB = true;
-            pendB_tok = tok0;
-        } else {
-            mul_fin(FIN_NO, q, WB, IB, cB, accB, accA, 0.0f, 0.0f, nullptr, 0);
-        }
-    };
-
-    x_issue(0);
-    w_issue(0, tileA, haveA, WA0, IA0, cA0);
-    w_issue(0, tileB, haveB, WB0, IB0, cB0);
-    x_commit(0);
-    wait_global_loads();
-    __syncthreads();
-    for (int p = 0; p < total; p += 2) {
-        {
-            const bool nxt = p + 1 < total;
-            if (nxt) {
-                x_issue(p + 1);
-                if (reload || p + 1 < 2) {
-                    w_issue(p + 1, tileA, haveA, WA1, IA1, cA1);
-                    w_issue(p + 1, tileB, haveB, WB1, IB1, cB1);
-                }
-            }
-            phase(p, WA0, IA0, cA0, WB0, IB0, cB0);
-            if (nxt) x_commit(p + 1);
-            wait_global_loads();
-            __syncthreads();
-        }
-        if (p + 1 >= total) break;
-        {
-            const bool nxt = p + 2 < total;
-            if (nxt) {
-                x_issue(p + 2);
-                if (reload) {
-                    w_issue(p + 2, tileA, haveA, WA0, IA0, cA0);
-                    w_issue(p + 2, tileB, haveB, WB0, IB0, cB0);
-                }
-            }
-            phase(p + 1, WA1, IA1, cA1, WB1, IB1, cB1);
-            if (nxt) x_commit(p + 2);
-            wait_global_loads();
-            __syncthreads();
-        }
-    }
-    // the last token tile's B is still pending
-    if (pendB && storeB) {
-        if (a.out_vec_ok && pendB_tok + PIPE_TM <= a.M) {
-            uint8_t* o = out_ptr(nB, pendB_tok);
-#pragma unroll
-            for (int i = 0; i < PIPE_PIECES; ++i) finish_quad<OUT, POST>(a, accB[i], scaleB, biasB, o, i, lds);
-        } else {
-            finish_slow(accB, nB, scaleB, biasB, pendB_tok, initB);
-        }
-    }
-}
-
-// =======================================================================================
-// Simple kernel (token tile 64, no software pipelining): kept as an independent second
-// implementation of the same layout; selected with spmm_set_tuning(h, 64, R).  Two
-// different tilings must agree bit for bit because int32 accumulation is order-free.
+// Simple kernel (token tile 64, one K segment in LDS, no software pipelining, table read
+// from global memory): an independent second implementation of the same layout, selected
+// with spmm_set_tuning(h, 64, 101 or 102).  Different tilings must agree bit for bit because
+// int32 accumulation is order-free.
 // =======================================================================================
 template <int TM, int NW, int R, int OUT, int POST>
 __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const KernelArgs a)
@@ -775,6 +509,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
         }
     }
 
+    const GlobalLut lut{a.lut};
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int n = row_of[r];
@@ -787,7 +522,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) {
             const int m0 = tok0 + 16 * i + 4 * g;
-            if (m0 < a.M) finish4<OUT, POST>(a, acc[r][i], s, bias, n, m0, a.lut);
+            if (m0 < a.M) finish4<OUT, POST>(a, acc[r][i], s, bias, n, m0, lut);
         }
     }
 }
@@ -795,66 +530,59 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
 // ---------------------------------------------------------------------------------------
 // host side: plan + dispatch
 // ---------------------------------------------------------------------------------------
-bool plan_supported(int token_tile, int row_tiles_per_wave)
+bool plan_supported(int token_tile, int variant)
 {
-    if (token_tile == 128)
-        return row_tiles_per_wave == 1 || row_tiles_per_wave == 2 || row_tiles_per_wave == 8 || row_tiles_per_wave == 16;
-    return (token_tile == 64) && (row_tiles_per_wave == 1 || row_tiles_per_wave == 2);
+    if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16;
+    if (token_tile == 64) return variant == 0 || variant == 8 || variant == 101 || variant == 102;
+    return false;
 }
 
-Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int force_r)
+Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant)
 {
     Plan p{};
-    p.token_tile = force_tm ? force_tm : PIPE_TM;
-    if (p.token_tile == PIPE_TM) {
-        // up to 4 steps per segment fit the 128-register budget of 16 waves; denser weights run
-        // with 8 waves (256 registers) and half as many rows per workgroup
-        p.max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? 6 : 8);
-        p.waves = (p.max_steps == 4) ? 16 : 8;
-        if (force_r == 8 || force_r == 16) p.waves = (force_r == 16 && p.max_steps != 4) ? 8 : force_r;
-        p.row_tiles_per_wave = 1;
-        if (force_r == 2 && p.max_steps <= 6) {   // fused variant: 8 waves x 2 row tiles (else: hint ignored)
-            p.waves = FUSED_NW;
-            p.row_tiles_per_wave = 2;
-        }
-        p.n_tok_tiles = (int)((M + PIPE_TM - 1) / PIPE_TM);
-        p.n_row_groups = (ntiles + p.waves * p.row_tiles_per_wave - 1) / (p.waves * p.row_tiles_per_wave);
-        // one workgroup per CU: S token-tile streams per row group
-        int S = num_cus / p.n_row_groups;
-        if (S < 1) S = 1;
-        if (S > p.n_tok_tiles) S = p.n_tok_tiles;
-        if (S >= 8) S -= S % 8;
-        p.n_streams = S;
-        p.xcd_map = (S % 8 == 0) ? 1 : 0;
-        p.workgroups = (int64_t)p.n_row_groups * S;
-    } else {
+    p.max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? 6 : 8);
+    p.token_tile = force_tm ? force_tm : 128;
+    if (p.token_tile == 64 && variant > 100) {   // simple kernel
         p.waves = 8;
-        p.row_tiles_per_wave = force_r ? force_r : 1;
-        p.max_steps = 0;
-        p.n_tok_tiles = (int)((M + p.token_tile - 1) / p.token_tile);
+        p.row_tiles_per_wave = variant - 100;
+        p.simple = 1;
+        p.n_tok_tiles = (int)((M + 63) / 64);
         p.n_row_groups = (ntiles + p.waves * p.row_tiles_per_wave - 1) / (p.waves * p.row_tiles_per_wave);
         p.n_streams = 0;
         p.xcd_map = 1;
         p.workgroups = (int64_t)8 * p.n_row_groups * ((p.n_tok_tiles + 7) / 8);
+        return p;
     }
+    p.row_tiles_per_wave = 1;
+    int wg_per_cu = 1;
+    if (p.token_tile == 128) {
+        // up to 4 steps per segment fit the 128-register budget of 16 waves; denser weights run
+        // with 8 waves (256 registers) and half as many rows per workgroup
+        p.waves = (p.max_steps == 4) ? 16 : 8;
+        if (variant == 8) p.waves = 8;
+    } else {
+        p.waves = 8;      // 80 KB of LDS: two workgroups per CU
+        wg_per_cu = 2;
+    }
+    p.n_tok_tiles = (int)((M + p.token_tile - 1) / p.token_tile);
+    p.n_row_groups = (ntiles + p.waves - 1) / p.waves;
+    // S token-tile streams per row group, enough workgroups to fill every CU once
+    int S = (num_cus * wg_per_cu) / p.n_row_groups;
+    if (S < 1) S = 1;
+    if (S > p.n_tok_tiles) S = p.n_tok_tiles;
+    if (S >= 8) S -= S % 8;
+    p.n_streams = S;
+    p.xcd_map = (S % 8 == 0) ? 1 : 0;
+    p.workgroups = (int64_t)p.n_row_groups * S;
     return p;
 }
 
-template <int NW, int MAXS>
+template <int TM, int NW, int MAXS>
 struct PipeLaunch {
     template <int OUT, int POST>
     static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
     {
-        hipLaunchKernelGGL((spmm_rowtile_mfma<NW, MAXS, OUT, POST>), grid, block, 0, st, a);
-    }
-};
-
-template <int MAXS>
-struct FusedLaunch {
-    template <int OUT, int POST>
-    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
-    {
-        hipLaunchKernelGGL((spmm_rowtile_mfma_fused<MAXS, OUT, POST>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST>), grid, block, 0, st, a);
     }
 };
 
@@ -897,22 +625,23 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_posto
     a.n_streams = plan.n_streams;
     a.xcd_map = plan.xcd_map;
     const dim3 grid((unsigned)plan.workgroups), block((unsigned)plan.waves * 64);
-    if (plan.token_tile == PIPE_TM) {
-        if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
-        if (plan.row_tiles_per_wave == 2 && plan.max_steps == 4) dispatch_epilogue<FusedLaunch<4>>(out_type, postop, grid, block, st, a);
-        else if (plan.row_tiles_per_wave == 2 && plan.max_steps == 6) dispatch_epilogue<FusedLaunch<6>>(out_type, postop, grid, block, st, a);
-        else if (plan.row_tiles_per_wave == 2) return (int)hipErrorInvalidValue;
-        else if (plan.waves == 16 && plan.max_steps == 4) dispatch_epilogue<PipeLaunch<16, 4>>(out_type, postop, grid, block, st, a);
-        else if (plan.waves == 8 && plan.max_steps == 4) dispatch_epilogue<PipeLaunch<8, 4>>(out_type, postop, grid, block, st, a);
-        else if (plan.waves == 8 && plan.max_steps == 6) dispatch_epilogue<PipeLaunch<8, 6>>(out_type, postop, grid, block, st, a);
-        else if (plan.waves == 8 && plan.max_steps == 8) dispatch_epilogue<PipeLaunch<8, 8>>(out_type, postop, grid, block, st, a);
+    if (plan.simple) {
+        if (plan.row_tiles_per_wave == 1) dispatch_epilogue<SimpleLaunch<1>>(out_type, postop, grid, block, st, a);
+        else if (plan.row_tiles_per_wave == 2) dispatch_epilogue<SimpleLaunch<2>>(out_type, postop, grid, block, st, a);
         else return (int)hipErrorInvalidValue;
-    } else if (plan.token_tile == 64 && plan.waves == 8 && plan.row_tiles_per_wave == 1) {
-        dispatch_epilogue<SimpleLaunch<1>>(out_type, postop, grid, block, st, a);
-    } else if (plan.token_tile == 64 && plan.waves == 8 && plan.row_tiles_per_wave == 2) {
-        dispatch_epilogue<SimpleLaunch<2>>(out_type, postop, grid, block, st, a);
-    } else {
-        return (int)hipErrorInvalidValue;
+        return (int)hipGetLastError();
+    }
+    if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
+    const int key = plan.token_tile * 10000 + plan.waves * 100 + plan.max_steps;
+    switch (key) {
+    case 1281604: dispatch_epilogue<PipeLaunch<128, 16, 4>>(out_type, postop, grid, block, st, a); break;
+    case 1280804: dispatch_epilogue<PipeLaunch<128, 8, 4>>(out_type, postop, grid, block, st, a); break;
+    case 1280806: dispatch_epilogue<PipeLaunch<128, 8, 6>>(out_type, postop, grid, block, st, a); break;
+    case 1280808: dispatch_epilogue<PipeLaunch<128, 8, 8>>(out_type, postop, grid, block, st, a); break;
+    case 640804: dispatch_epilogue<PipeLaunch<64, 8, 4>>(out_type, postop, grid, block, st, a); break;
+    case 640806: dispatch_epilogue<PipeLaunch<64, 8, 6>>(out_type, postop, grid, block, st, a); break;
+    case 640808: dispatch_epilogue<PipeLaunch<64, 8, 8>>(out_type, postop, grid, block, st, a); break;
+    default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();
 }

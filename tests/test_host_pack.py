@@ -158,7 +158,10 @@ def test_pack_argument_errors():
     ep = sp.make_epilogue()
     assert sp.spmm_run_status(hh, 16, 4, 4, ep, 16, 4) == sp.SPMM_E_ARG      # host-only handle
     assert L.spmm_set_tuning(hh, 48, 0) == sp.SPMM_E_UNSUPPORTED
-    assert L.spmm_set_tuning(hh, 64, 2) == sp.SPMM_OK
+    assert L.spmm_set_tuning(hh, 128, 101) == sp.SPMM_E_UNSUPPORTED
+    assert L.spmm_set_tuning(hh, 0, 8) == sp.SPMM_E_ARG
+    assert L.spmm_set_tuning(hh, 64, 102) == sp.SPMM_OK
+    assert L.spmm_set_tuning(hh, 0, 0) == sp.SPMM_OK
     sp.spmm_destroy(hh)
 
 
