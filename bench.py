@@ -36,9 +36,12 @@ HBM_PEAK_GBS = 8000.0
 INT8_MFMA_PEAK_TOPS = 5000.0
 ROTATE = 3   # distinct X/out buffer sets per SpMM (6 calls x 3 sets x ~30 MB > 256 MB of cache)
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), or None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size) of the kernel
+# instantiations of the default workload, from the rocprofv3 --pmc runs summarised under profiles/.
+MEASURED_TRAFFIC_BYTES = {
+    "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)": 36369866,
+    "void spmm::spmm_rowtile_mfma<128, 8, 6, 2, 1>(spmm::KernelArgs)": 50119321,
+}
 
 
 def algorithmic_bytes(N, K, M, nnz_blocks, out_elem):
@@ -53,7 +56,11 @@ def main() -> int:
     ap.add_argument("--workload", default="large", choices=["large", "base", "mini"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--tuning", default="", help="token_tile,row_tiles_per_wave override (0 = automatic)")
+    ap.add_argument("--tuning", default="", help="token_tile,variant override passed to spmm_set_tuning")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    ap.add_argument("--only", default="", help="keep only the calls whose case name contains this substring")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 256 MiB device copy (profiling aid: scales FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the SpMM shards trivially over tokens or output "
@@ -82,6 +89,12 @@ def main() -> int:
     else:
         cases = wl.mini_cases()
         wname = "bert_mini_ffn_pair_m1024_s80"
+    if args.only:
+        cases = [c for c in cases if args.only in c.name]
+        wname += "[" + args.only + "]"
+        if not cases:
+            print("bench.py: --only matched no case", file=sys.stderr)
+            return 2
     out_elem = {"s32": 4, "f32": 4, "s8": 1, "u8": 1}
     tdt = {"s32": torch.int32, "f32": torch.float32, "s8": torch.int8, "u8": torch.uint8}
 
@@ -111,34 +124,69 @@ def main() -> int:
 
     def launch(c, it):
         j = it % ROTATE
-        sp.spmm_run(c["h"], c["Xs"][j], c["M"], c["M"], c["ep"], c["outs"][j], c["M"], stream.cuda_stream)
+        sp.spmm_run(c["h"], c["Xs"][j], c["M"], c["M"], c["ep"], c["outs"][j], c["M"],
+                    torch.cuda.current_stream().cuda_stream)
 
-    # ------------------------------------------------------------------ warm-up, then timed region
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # one plain copy kernel moving 256 MiB each way
+        torch.cuda.synchronize()
+        del src, dst
+
+    # ------------------------------------------------------------------ warm-up
     for it in range(args.warmup):
         for c in calls:
             launch(c, it)
     torch.cuda.synchronize()
-
     nc = len(calls)
+
+    # ------------------------------------------------------------------ timed region A: K steps, eager launches,
+    # HIP events on the launch stream around every kernel (per-kernel durations for the roofline)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(nc + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for it in range(args.steps):
-        ev[it][0].record(stream)
+        ev[it][0].record()
         for ci, c in enumerate(calls):
             launch(c, it)
-            ev[it][ci + 1].record(stream)
+            ev[it][ci + 1].record()
     torch.cuda.synchronize()
     wall_s = time.perf_counter() - t0
-    step_ms = [ev[it][0].elapsed_time(ev[it][nc]) for it in range(args.steps)]
-    # steps are back to back on one stream: total = first event of step 0 .. last event of the last step
-    total_ms = ev[0][0].elapsed_time(ev[args.steps - 1][nc])
-    ms_per_step = total_ms / args.steps
+    eager_ms_per_step = ev[0][0].elapsed_time(ev[args.steps - 1][nc]) / args.steps
     per_call_us = np.array([[ev[it][ci].elapsed_time(ev[it][ci + 1]) * 1e3 for ci in range(nc)]
                             for it in range(args.steps)])
     avg_us = per_call_us.mean(axis=0)
     med_us = np.median(per_call_us, axis=0)
     min_us = per_call_us.min(axis=0)
+
+    # ------------------------------------------------------------------ timed region B: the same K steps replayed from
+    # HIP graphs (one graph per buffer rotation; spmm_run allocates nothing and never synchronises, so it
+    # captures as is).  Launch-bound sequences of 10-50 us kernels are what graphs are for; this is `value`.
+    graph_ms_per_step = None
+    if not args.no_graph:
+        try:
+            graphs = []
+            for j in range(ROTATE):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for c in calls:
+                        launch(c, j)
+                graphs.append(g)
+            for it in range(max(2, args.warmup // 2)):
+                graphs[it % ROTATE].replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for it in range(args.steps):
+                graphs[it % ROTATE].replay()
+            e1.record()
+            torch.cuda.synchronize()
+            graph_ms_per_step = e0.elapsed_time(e1) / args.steps
+        except Exception as exc:   # fall back to the eager figure
+            print("bench.py: graph capture unavailable (%r); reporting eager launches" % (exc,), file=sys.stderr)
+    ms_per_step = graph_ms_per_step if graph_ms_per_step is not None else eager_ms_per_step
 
     dense_ops = sum(c["dense_ops"] for c in calls)
     nnz_ops = sum(c["nnz_ops"] for c in calls)
@@ -184,14 +232,31 @@ def main() -> int:
             "speedup_vs_dense_gemm": (round(dense[key]["us"] / t, 2) if key in dense and "us" in dense[key] else None),
             "sha256": {"W": wl.sha256(c["d"]["W"])[:16], "X": wl.sha256(c["d"]["X"])[:16]},
         })
-    tot_bytes = sum(c["bytes"] for c in calls)
-    tot_us = float(avg_us.sum())
-    achieved = tot_bytes / (tot_us * 1e-6) / 1e9
+    # roofline of the dominant kernel instantiation (largest share of the step): algorithmic bytes of
+    # its launches / their summed durations = bytes per launch / average launch duration
+    by_kernel = {}
+    for ci, c in enumerate(calls):
+        name = sp.spmm_kernel_variant(c["h"], c["M"], c["case"].out_type, c["case"].postop)
+        k = by_kernel.setdefault(name, {"bytes": 0.0, "us": 0.0, "launches": 0, "nnz_ops": 0.0})
+        k["bytes"] += c["bytes"]
+        k["us"] += float(avg_us[ci])
+        k["launches"] += 1
+        k["nnz_ops"] += c["nnz_ops"]
+    dom_name = max(by_kernel, key=lambda n: by_kernel[n]["us"])
+    dom = by_kernel[dom_name]
+    achieved = dom["bytes"] / (dom["us"] * 1e-6) / 1e9
     roofline = {
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES,
-        "kernel": sp.spmm_kernel_name(), "launches_per_step": nc,
-        "avg_launch_us": round(tot_us / nc, 3), "algorithmic_bytes_per_launch": int(tot_bytes / nc),
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dom_name),
+        "kernel": dom_name, "launches_per_step": dom["launches"],
+        "avg_launch_us": round(dom["us"] / dom["launches"], 3),
+        "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"]),
+        "int8_mfma_frac": round(dom["nnz_ops"] / (dom["us"] * 1e-6) / (INT8_MFMA_PEAK_TOPS * 1e12), 4),
+        "timing": "HIP events around each eager launch (includes the dispatch gap between kernels)",
+        "other_kernels": {n: {"avg_launch_us": round(v["us"] / v["launches"], 3),
+                              "frac": round(v["bytes"] / (v["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                              "traffic": MEASURED_TRAFFIC_BYTES.get(n)}
+                          for n, v in by_kernel.items() if n != dom_name},
     }
 
     # ------------------------------------------------------------------ CPU baseline: the oracle on the host cores
@@ -232,7 +297,10 @@ def main() -> int:
                    "buffer_rotation": ROTATE},
         "nonzero_tops": round(nnz_tops, 2),
         "roofline": roofline, "cpu_baseline": cpu, "dense_int8_gemm": dense, "per_call": rows,
-        "step_ms_median": round(float(np.median(step_ms)), 5), "host_wall_s": round(wall_s, 4),
+        "ms_per_step_eager_with_events": round(eager_ms_per_step, 5),
+        "ms_per_step_graph": (round(graph_ms_per_step, 5) if graph_ms_per_step is not None else None),
+        "launch_mode": ("hip_graph_replay" if graph_ms_per_step is not None else "eager"),
+        "host_wall_s_eager": round(wall_s, 4),
     }
     print(json.dumps(line))
     return 0

@@ -167,8 +167,14 @@ spmm_status_t spmm_plan(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
  * concurrent spmm_run on the same handle. */
 spmm_status_t spmm_set_tuning(spmm_handle_t *h, int32_t token_tile, int32_t variant);
 
-/* Name of the device kernel spmm_run launches for this configuration (for profilers). */
+/* Base name of the device kernels spmm_run launches (for profilers). */
 const char *spmm_kernel_name(void);
+
+/* Full name, as a profiler prints it, of the kernel instantiation spmm_run would launch for
+ * M tokens with this output type and post-operator.  buf is HOST memory of buflen bytes; the
+ * name is NUL-terminated and truncated if it does not fit. */
+spmm_status_t spmm_kernel_variant(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
+                                  spmm_postop_t postop, char *buf, int64_t buflen);
 
 void spmm_destroy(spmm_handle_t *h); /* NULL is allowed */
 

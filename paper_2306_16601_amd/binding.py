@@ -29,7 +29,7 @@ OUT_TYPES = {"s32": SPMM_OUT_S32, "f32": SPMM_OUT_F32, "s8": SPMM_OUT_S8, "u8": 
 EXPORTS = (
     "spmm_pack", "spmm_pack_host", "spmm_unpack", "spmm_info", "spmm_layout_dims",
     "spmm_layout_export", "spmm_run", "spmm_make_gelu_lut", "spmm_plan", "spmm_set_tuning",
-    "spmm_kernel_name", "spmm_destroy", "spmm_status_string",
+    "spmm_kernel_name", "spmm_kernel_variant", "spmm_destroy", "spmm_status_string",
 )
 
 
@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.spmm_set_tuning.argtypes = [vp, i32, i32]
         L.spmm_kernel_name.restype = ctypes.c_char_p
         L.spmm_kernel_name.argtypes = []
+        L.spmm_kernel_variant.restype = ci
+        L.spmm_kernel_variant.argtypes = [vp, i64, ci, ci, ctypes.c_char_p, i64]
         L.spmm_destroy.restype = None
         L.spmm_destroy.argtypes = [vp]
         L.spmm_status_string.restype = ctypes.c_char_p
@@ -116,6 +118,14 @@ def spmm_status_string(status: int) -> str:
 
 def spmm_kernel_name() -> str:
     return lib().spmm_kernel_name().decode()
+
+
+def spmm_kernel_variant(handle: int, M: int, out_type="s32", postop="none") -> str:
+    ot = OUT_TYPES[out_type] if isinstance(out_type, str) else int(out_type)
+    po = POSTOPS[postop] if isinstance(postop, str) else int(postop)
+    buf = ctypes.create_string_buffer(256)
+    _check(lib().spmm_kernel_variant(handle, int(M), ot, po, buf, 256), "spmm_kernel_variant")
+    return buf.value.decode()
 
 
 def _pack(fn, W: np.ndarray, block) -> int:

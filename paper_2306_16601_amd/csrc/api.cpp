@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <new>
 
@@ -248,6 +249,23 @@ spmm_status_t spmm_make_gelu_lut(float mid_scale, float out_scale, int32_t out_z
 }
 
 const char* spmm_kernel_name(void) { return "spmm_rowtile_mfma"; }
+
+spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t out_type, spmm_postop_t postop,
+                                  char* buf, int64_t buflen)
+{
+    if (!h || M <= 0 || !buf || buflen <= 0) return SPMM_E_ARG;
+    if (out_type < SPMM_OUT_S32 || out_type > SPMM_OUT_U8) return SPMM_E_ARG;
+    if (postop != SPMM_POST_NONE && postop != SPMM_POST_GELU) return SPMM_E_ARG;
+    const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r);
+    const int post = (out_type == SPMM_OUT_S32) ? 0 : (int)postop;   // S32 output ignores the post-operator
+    if (p.simple)
+        std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_simple<64, %d, %d, %d, %d>(spmm::KernelArgs)",
+                      p.waves, p.row_tiles_per_wave, (int)out_type, post);
+    else
+        std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma<%d, %d, %d, %d, %d>(spmm::KernelArgs)",
+                      p.token_tile, p.waves, p.max_steps, (int)out_type, post);
+    return SPMM_OK;
+}
 
 void spmm_destroy(spmm_handle_t* h)
 {
