@@ -221,9 +221,10 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
     a.kc = h->kc; a.nseg = h->nseg; a.ntiles = h->ntiles;
     a.corr_mul = 128 - ep->x_zero_point;
     a.x_scale = ep->x_scale;
-    a.x_vec_ok = aligned(X_dev, 16) && (ldx % 16 == 0);
+    // fast paths use 16-byte accesses and 32-bit offsets
+    a.x_vec_ok = aligned(X_dev, 16) && (ldx % 16 == 0) && (h->bsr.K * ldx < ((int64_t)1 << 31));
     const int64_t esz = quant ? 1 : 4;
-    a.out_vec_ok = aligned(out_dev, 16) && ((ldo * esz) % 16 == 0);
+    a.out_vec_ok = aligned(out_dev, 16) && ((ldo * esz) % 16 == 0) && (h->bsr.N * ldo * esz < ((int64_t)1 << 31));
 
     const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r);
     const int rc = spmm::launch_spmm(p, a, ot, gelu ? SPMM_POST_GELU : SPMM_POST_NONE, hip_stream);

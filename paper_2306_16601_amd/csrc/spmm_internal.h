@@ -79,8 +79,8 @@ struct KernelArgs {
     int xcd_map;         // 1: workgroup ids are decoded so that a token-tile stream stays on one XCD
     int corr_mul;        // 128 - x_zero_point: the activations are multiplied as (x - 128)
     float x_scale, inv_out, inv_mid, out_zp_f;
-    int x_vec_ok;        // X base 16-byte aligned and ldx % 16 == 0
-    int out_vec_ok;      // out base 16-byte aligned and row pitch a multiple of 16 bytes
+    int x_vec_ok;        // X base 16-byte aligned, ldx % 16 == 0 and K * ldx < 2^31
+    int out_vec_ok;      // out base 16-byte aligned, row pitch a multiple of 16 bytes, whole output < 2^31 bytes
 };
 
 struct Plan {

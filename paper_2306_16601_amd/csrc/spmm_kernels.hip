@@ -211,13 +211,16 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
     asm volatile("" : "+v"(lane));
     const int g = lane >> 4, c = lane & 15;
     if constexpr (OUT == SPMM_OUT_S32) {
-        int32_t* o = (int32_t*)a.out + ((int64_t)(tile * TILE_ROWS + c) * a.ldo + tok0 + 4 * g);
+        // fast path: the whole output is < 2 GiB (checked on the host), 32-bit offsets suffice
+        const uint32_t off = (uint32_t)(tile * TILE_ROWS + c) * (uint32_t)a.ldo + (uint32_t)(tok0 + 4 * g);
+        int32_t* o = (int32_t*)a.out + off;
         if (tile * TILE_ROWS + c < a.N) {
 #pragma unroll
             for (int i = 0; i < G::PIECES; ++i) *(v4i*)(o + 16 * i) = acc[i];
         }
     } else if constexpr (OUT == SPMM_OUT_F32) {
-        float* o = (float*)a.out + ((int64_t)(tile * TILE_ROWS + c) * a.ldo + tok0 + 4 * g);
+        const uint32_t off = (uint32_t)(tile * TILE_ROWS + c) * (uint32_t)a.ldo + (uint32_t)(tok0 + 4 * g);
+        float* o = (float*)a.out + off;
         if (tile * TILE_ROWS + c < a.N) {
 #pragma unroll
             for (int i = 0; i < G::PIECES; ++i) {
@@ -239,7 +242,8 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
         const int rr = lane >> 2, rj = lane & 3;
         const uint32_t raddr = G::chunk(64 * wave + 4 * rr + (rj ^ (rr >> 2)));
         const int orow = tile * TILE_ROWS + rr;
-        uint8_t* o = (uint8_t*)a.out + ((int64_t)orow * a.ldo + tok0 + 16 * rj);
+        const uint32_t off = (uint32_t)orow * (uint32_t)a.ldo + (uint32_t)(tok0 + 16 * rj);
+        uint8_t* o = (uint8_t*)a.out + off;
 #pragma unroll
         for (int h = 0; h < G::HALVES; ++h) {
 #pragma unroll
@@ -327,11 +331,12 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         const int k0 = seg * SEGMENT_ROWS;
         const int last = min(SEGMENT_ROWS, a.K - k0) - 1;
         if (a.x_vec_ok && tok0 + TM <= a.M) {
-            const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0 + x_piece * 16;
+            // fast path: K * ldx < 2 GiB (checked on the host), 32-bit offsets from a uniform base
+            const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0;
 #pragma unroll
             for (int u = 0; u < XLOADS; ++u) {
                 const int row = min(x_row0 + u * ROWS_PER_PASS, last);
-                xr[u] = *(const v4i*)(src + (int64_t)row * a.ldx);
+                xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(x_piece * 16)));
             }
         } else {
 #pragma unroll
