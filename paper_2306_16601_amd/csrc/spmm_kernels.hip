@@ -313,7 +313,9 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     v4i A0[MAXS], A1[MAXS];
     uint32_t I0[MAXS], I1[MAXS];
     int n0 = 0, n1 = 0;
-    v4i xr[XLOADS];
+    constexpr int XH = XLOADS / 2;   // the prefetch is issued and committed in two halves
+    static_assert(XH * 2 == XLOADS, "even number of prefetch loads");
+    v4i xr[XH];
     v4i acc[PIECES];
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
@@ -322,10 +324,12 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     const int x_row0 = tid / PIECES, x_piece = tid % PIECES;
     const uint32_t x_lds0 = G::X0 + (uint32_t)x_row0 * G::STRIDE + x_piece * 16;
 
-    // ---- global loads of the activations of phase q into registers.  The common case (16-byte
-    // aligned rows, full token tile) is branch-free so that all loads are in flight together;
-    // rows past the end of K are redirected to the last valid row (never multiplied).
-    auto x_issue = [&](const int q) {
+    // ---- global loads of half h of the activations of phase q into registers.  The common case
+    // (16-byte aligned rows, full token tile) is branch-free so that all loads are in flight
+    // together; rows past the end of K are redirected to the last valid row (never multiplied).
+    // Two halves (first issued at the start of the previous phase, second half-way through its
+    // multiply) keep only XH prefetch registers live.
+    auto x_issue = [&](const int q, const int h) {
         const int j = q / a.nseg, seg = q - j * a.nseg;
         const int tok0 = (stream + j * S) * TM;
         const int k0 = seg * SEGMENT_ROWS;
@@ -334,23 +338,23 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
             // fast path: K * ldx < 2 GiB (checked on the host), 32-bit offsets from a uniform base
             const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0;
 #pragma unroll
-            for (int u = 0; u < XLOADS; ++u) {
-                const int row = min(x_row0 + u * ROWS_PER_PASS, last);
+            for (int u = 0; u < XH; ++u) {
+                const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
                 xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(x_piece * 16)));
             }
         } else {
 #pragma unroll
-            for (int u = 0; u < XLOADS; ++u) {
-                const int row = min(x_row0 + u * ROWS_PER_PASS, last);
+            for (int u = 0; u < XH; ++u) {
+                const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
                 xr[u] = load_x16(a, k0 + row, tok0 + x_piece * 16);
             }
         }
     };
     // ---- ... and from registers into LDS buffer q % 2, as x - 128
-    auto x_commit = [&](const int q) {
-        uint8_t* buf = lds + (q & 1) * G::BUF + x_lds0;
+    auto x_commit = [&](const int q, const int h) {
+        uint8_t* buf = lds + (q & 1) * G::BUF + x_lds0 + h * XH * ROWS_PER_PASS * G::STRIDE;
 #pragma unroll
-        for (int u = 0; u < XLOADS; ++u)
+        for (int u = 0; u < XH; ++u)
             *(v4i*)(buf + u * ROWS_PER_PASS * G::STRIDE) = xr[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
     };
     // ---- compressed weights + activation-row indices of (tile, segment of phase q).  Loads are
@@ -370,8 +374,10 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
             I[s] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
         }
     };
-    // ---- multiply phase q: gather + transpose out of LDS, PIECES matrix instructions per step
-    auto multiply = [&](const int q, const v4i (&A)[MAXS], const uint32_t (&I)[MAXS], const int cnt) {
+    // ---- multiply phase q: gather + transpose out of LDS, PIECES matrix instructions per step.
+    // Half-way (after step slot MAXS/2 - 1, executed or not) the first half of the next phase's
+    // activations is committed and the second half's loads are issued.
+    auto multiply = [&](const int q, const bool nxt, const v4i (&A)[MAXS], const uint32_t (&I)[MAXS], const int cnt) {
         const uint32_t base = G::X0 + (uint32_t)(q & 1) * G::BUF + (c & 1) * 8;
 #pragma unroll
         for (int s = 0; s < MAXS; ++s) {
@@ -386,6 +392,10 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
                     const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
                     acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, A[s], acc[i], 0, 0, 0);
                 }
+            }
+            if (s == MAXS / 2 - 1 && nxt) {
+                x_commit(q + 1, 0);
+                x_issue(q + 1, 1);
             }
         }
     };
@@ -411,20 +421,22 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     };
     const bool reload = a.nseg > 2;   // otherwise set q % 2 always holds segment q % nseg
 
-    x_issue(0);
+    x_issue(0, 0);
     w_issue(0, A0, I0, n0);
-    x_commit(0);
+    x_commit(0, 0);
+    x_issue(0, 1);
+    x_commit(0, 1);
     wait_global_loads();
     __syncthreads();
     for (int p = 0; p < total; p += 2) {
         {   // even phase: register set 0, LDS buffer 0
             const bool nxt = p + 1 < total;
             if (nxt) {
-                x_issue(p + 1);
+                x_issue(p + 1, 0);
                 if (reload || p + 1 < 2) w_issue(p + 1, A1, I1, n1);
             }
-            multiply(p, A0, I0, n0);
-            if (nxt) x_commit(p + 1);
+            multiply(p, nxt, A0, I0, n0);
+            if (nxt) x_commit(p + 1, 1);
             wait_global_loads();   // before the output stores: they must not be waited for
             finish(p);
             __syncthreads();
@@ -433,11 +445,11 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         {   // odd phase: register set 1, LDS buffer 1
             const bool nxt = p + 2 < total;
             if (nxt) {
-                x_issue(p + 2);
+                x_issue(p + 2, 0);
                 if (reload) w_issue(p + 2, A0, I0, n0);
             }
-            multiply(p + 1, A1, I1, n1);
-            if (nxt) x_commit(p + 2);
+            multiply(p + 1, nxt, A1, I1, n1);
+            if (nxt) x_commit(p + 2, 1);
             wait_global_loads();
             finish(p + 1);
             __syncthreads();
@@ -563,7 +575,7 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
     if (p.token_tile == 128) {
         // up to 4 steps per segment fit the 128-register budget of 16 waves; denser weights run
         // with 8 waves (256 registers) and half as many rows per workgroup
-        p.waves = (p.max_steps == 4) ? 16 : 8;
+        p.waves = (p.max_steps <= 6) ? 16 : 8;
         if (variant == 8) p.waves = 8;
     } else {
         p.waves = 8;      // 80 KB of LDS: two workgroups per CU
@@ -640,6 +652,7 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_posto
     const int key = plan.token_tile * 10000 + plan.waves * 100 + plan.max_steps;
     switch (key) {
     case 1281604: dispatch_epilogue<PipeLaunch<128, 16, 4>>(out_type, postop, grid, block, st, a); break;
+    case 1281606: dispatch_epilogue<PipeLaunch<128, 16, 6>>(out_type, postop, grid, block, st, a); break;
     case 1280804: dispatch_epilogue<PipeLaunch<128, 8, 4>>(out_type, postop, grid, block, st, a); break;
     case 1280806: dispatch_epilogue<PipeLaunch<128, 8, 6>>(out_type, postop, grid, block, st, a); break;
     case 1280808: dispatch_epilogue<PipeLaunch<128, 8, 8>>(out_type, postop, grid, block, st, a); break;
