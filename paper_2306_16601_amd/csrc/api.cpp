@@ -263,8 +263,9 @@ spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t 
         std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_simple<64, %d, %d, %d, %d>(spmm::KernelArgs)",
                       p.waves, p.row_tiles_per_wave, (int)out_type, post);
     else
+        // (8-wave configurations run 5-step weights with the 6-step instantiation)
         std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma<%d, %d, %d, %d, %d>(spmm::KernelArgs)",
-                      p.token_tile, p.waves, p.max_steps, (int)out_type, post);
+                      p.token_tile, p.waves, (p.waves == 8 && p.max_steps == 5) ? 6 : p.max_steps, (int)out_type, post);
     return SPMM_OK;
 }
 

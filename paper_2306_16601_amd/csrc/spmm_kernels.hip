@@ -557,7 +557,7 @@ bool plan_supported(int token_tile, int variant)
 Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant)
 {
     Plan p{};
-    p.max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? 6 : 8);
+    p.max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? max_steps_per_segment : 8);
     p.token_tile = force_tm ? force_tm : 128;
     if (p.token_tile == 64 && variant > 100) {   // simple kernel
         p.waves = 8;
@@ -652,11 +652,14 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_posto
     const int key = plan.token_tile * 10000 + plan.waves * 100 + plan.max_steps;
     switch (key) {
     case 1281604: dispatch_epilogue<PipeLaunch<128, 16, 4>>(out_type, postop, grid, block, st, a); break;
+    case 1281605: dispatch_epilogue<PipeLaunch<128, 16, 5>>(out_type, postop, grid, block, st, a); break;
     case 1281606: dispatch_epilogue<PipeLaunch<128, 16, 6>>(out_type, postop, grid, block, st, a); break;
     case 1280804: dispatch_epilogue<PipeLaunch<128, 8, 4>>(out_type, postop, grid, block, st, a); break;
+    case 1280805: dispatch_epilogue<PipeLaunch<128, 8, 6>>(out_type, postop, grid, block, st, a); break;
     case 1280806: dispatch_epilogue<PipeLaunch<128, 8, 6>>(out_type, postop, grid, block, st, a); break;
     case 1280808: dispatch_epilogue<PipeLaunch<128, 8, 8>>(out_type, postop, grid, block, st, a); break;
     case 640804: dispatch_epilogue<PipeLaunch<64, 8, 4>>(out_type, postop, grid, block, st, a); break;
+    case 640805: dispatch_epilogue<PipeLaunch<64, 8, 6>>(out_type, postop, grid, block, st, a); break;
     case 640806: dispatch_epilogue<PipeLaunch<64, 8, 6>>(out_type, postop, grid, block, st, a); break;
     case 640808: dispatch_epilogue<PipeLaunch<64, 8, 8>>(out_type, postop, grid, block, st, a); break;
     default: return (int)hipErrorInvalidValue;
