@@ -158,10 +158,11 @@ spmm_status_t spmm_plan(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
 /* Override the automatic choice of kernel configuration for later spmm_run calls on this
  * handle; (0, 0) restores the automatic choice.
  *   token_tile 128: pipelined kernel, one workgroup per CU; variant 0 = automatic, 8 or 16 =
- *                   waves per workgroup (16 only holds weights with <= 4 steps per segment,
+ *                   waves per workgroup (16 only holds weights with <= 6 steps per segment,
  *                   denser weights silently use 8).
- *   token_tile  64: variant 0 or 8 = pipelined kernel with two workgroups per CU;
- *                   variant 101 / 102 = the simple, unpipelined kernel with 1 / 2 row tiles
+ *   token_tile  96: the same kernel on 96-token tiles, variant 0 or 16 (16 waves; denser
+ *                   weights silently use token tile 128 with 8 waves).
+ *   token_tile  64: variant 101 / 102 = the simple, unpipelined kernel with 1 / 2 row tiles
  *                   per wave (an independent second implementation for cross-checks).
  * Unsupported values return SPMM_E_UNSUPPORTED and change nothing.  Not thread-safe against
  * concurrent spmm_run on the same handle. */

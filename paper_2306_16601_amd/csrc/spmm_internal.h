@@ -59,7 +59,7 @@ void bsr_to_dense(const Bsr& b, int8_t* W, int64_t ldw);
 void layout_from_bsr(const Bsr& b, int kc, HostLayout& out);
 
 // ---------------------------------------------------------------------------------------
-// Kernel launch interface (implemented in spmm_kernels.hip).
+// Kernel launch interface (plan and dispatch in spmm_plan.hip, kernels in spmm_kernels.h).
 // ---------------------------------------------------------------------------------------
 struct KernelArgs {
     const uint8_t* vals;
@@ -84,7 +84,7 @@ struct KernelArgs {
 };
 
 struct Plan {
-    int token_tile;          // TM of the pipelined kernel (128: one workgroup per CU, 64: two), or 64 for the simple kernel
+    int token_tile;          // TM of the pipelined kernel (128 or 96), or 64 for the simple kernel
     int row_tiles_per_wave;  // 1 (pipelined) or 1 / 2 (simple kernel)
     int waves;               // NW
     int simple;              // 1: simple kernel
@@ -93,8 +93,8 @@ struct Plan {
     int64_t workgroups;
 };
 
-// variant: 0 = automatic, 8 / 16 = waves per workgroup (pipelined), 101 / 102 = simple kernel
-// with 1 / 2 row tiles per wave (token tile 64 only)
+// variant: 0 = automatic, 8 / 16 = waves per workgroup (pipelined, token tile 128 or 96),
+// 101 / 102 = simple kernel with 1 / 2 row tiles per wave (token tile 64 only)
 bool plan_supported(int token_tile, int variant);
 Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant);
 // Launches the SpMM kernel; returns a hipError_t value as int (0 = success).

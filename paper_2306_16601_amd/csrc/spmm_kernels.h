@@ -31,6 +31,8 @@
 // 8 bytes; result lane p receives, as byte t, byte (p % 8) of the 8 bytes addressed by
 // source position 2t + p / 8.  With source position 2t + h pointing at tokens 8h .. 8h+7
 // of activation row k_t, result lane p holds token p of rows k_0 .. k_7.
+#pragma once
+
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -152,17 +154,18 @@ __device__ __forceinline__ v4i load_x16(const KernelArgs& a, const int krow, con
 // with at most two segments they are loaded once per workgroup and reused for every token
 // tile, otherwise they are prefetched one phase ahead.
 //
-// Two LDS geometries:
-//   TM = 128: 16 (or 8) waves, one workgroup per CU; table at LDS offset 0, buffers behind.
-//   TM =  64: 8 waves and 80 KB, so that TWO workgroups share a CU: while one is in its
-//             VALU-bound post-operators or waits at a barrier, the other one keeps the LDS
-//             and the matrix cores busy.
+// Two token-tile widths, both with one workgroup per CU, the table at LDS offset 0 and the
+// buffers behind it:
+//   TM = 128: the default.
+//   TM =  96: chosen by the plan when it divides the tokens into a number of tiles that fills
+//             the CUs more evenly (6144 tokens and 4 row groups: 256 workgroups instead of 192).
+//             A row is 6 pieces of 16 bytes; 3/4 of the threads stage them.
 // Every LDS row has 16 spare bytes behind its TM tokens (the pitch TM + 16 makes consecutive
-// rows start 4 banks apart).  These spare chunks carry the output staging for 1-byte outputs
-// (and, for TM = 64 where no LDS is left, the table): wave w transposes its 16 rows x 64
-// tokens through chunks 64w .. 64w+63 so that a row's tokens leave in 64-byte runs instead
-// of 4-byte pieces.  Staging row r, 16-token piece j lives in chunk 4r + (j ^ (r >> 2)): with
-// both pitches the 4-byte writes and the 16-byte reads then touch every LDS bank once.
+// rows start 4 banks apart).  These spare chunks carry the output staging for 1-byte outputs:
+// wave w transposes its 16 rows x 64 tokens through chunks 64w .. 64w+63 so that a row's
+// tokens leave in 64-byte runs (32 for the last third of a 96-token tile) instead of 4-byte
+// pieces.  Staging row r, 16-token piece j lives in chunk 4r + (j ^ (r >> 2)): with both
+// pitches the 4-byte writes and the 16-byte reads then touch every LDS bank once.
 // =======================================================================================
 template <int TM>
 struct Geo;
@@ -179,15 +182,13 @@ struct Geo<128> {
 };
 
 template <>
-struct Geo<64> {
-    static constexpr int STRIDE = 80, PIECES = 4, HALVES = 1;
-    static constexpr int BUF = SEGMENT_ROWS * STRIDE;   // 40960
-    static constexpr int X0 = 0;
-    static constexpr int LDS = 2 * BUF;                 // 81920: two workgroups per CU
-    // table entry e in the spare chunk of row e / 16 of buffer 0: 64 distinct banks for 64 dwords
-    static __device__ __forceinline__ uint32_t lut_addr(uint32_t key) { return key + (key >> 4) * 64 + 64; }
-    // staging chunk n in [0, 512): behind row n of buffer 1
-    static __device__ __forceinline__ uint32_t chunk(uint32_t n) { return BUF + n * STRIDE + 64; }
+struct Geo<96> {
+    static constexpr int STRIDE = 112, PIECES = 6, HALVES = 2;
+    static constexpr int BUF = SEGMENT_ROWS * STRIDE;   // 57344
+    static constexpr int X0 = 256;
+    static constexpr int LDS = X0 + 2 * BUF;
+    static __device__ __forceinline__ uint32_t lut_addr(uint32_t key) { return key; }
+    static __device__ __forceinline__ uint32_t chunk(uint32_t n) { return X0 + n * STRIDE + 96; }
 };
 
 template <int TM>
@@ -249,6 +250,7 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = 4 * h + j;
+                if (i >= G::PIECES) continue;   // (a 96-token tile ends after piece 5)
                 uint32_t word = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
@@ -256,7 +258,7 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
                 *(uint32_t*)(lds + wbase + (uint32_t)(j ^ wsw) * G::STRIDE) = word;
             }
             const v4i v = *(const v4i*)(lds + raddr);   // same wave: LDS operations complete in order
-            if (orow < a.N) *(v4i*)(o + 64 * h) = v;
+            if (orow < a.N && 4 * h + rj < G::PIECES) *(v4i*)(o + 64 * h) = v;
         }
     }
 }
@@ -267,9 +269,12 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     using G = Geo<TM>;
     constexpr int NTHREADS = NW * 64;
     constexpr int PIECES = G::PIECES;
-    constexpr int ROWS_PER_PASS = NTHREADS / PIECES;                // activation rows one load pass covers
-    constexpr int XLOADS = SEGMENT_ROWS / ROWS_PER_PASS;            // 16-byte loads per thread and phase
-    static_assert(XLOADS * ROWS_PER_PASS == SEGMENT_ROWS, "threads must tile a segment");
+    // activation rows one load pass covers: a power of two; with 6 pieces per row only
+    // ROWS_PER_PASS * 6 threads (whole waves) stage
+    constexpr int ROWS_PER_PASS = (NTHREADS / PIECES >= 128) ? 128 : 64;
+    constexpr int STAGERS = ROWS_PER_PASS * PIECES;
+    constexpr int XLOADS = SEGMENT_ROWS / ROWS_PER_PASS;            // 16-byte loads per staging thread and phase
+    static_assert(STAGERS <= NTHREADS && STAGERS % 64 == 0, "staging threads must be whole waves of the workgroup");
     __shared__ __attribute__((aligned(16))) uint8_t lds[G::LDS];
 
     const int tid = threadIdx.x;
@@ -321,6 +326,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
 
     // per-thread staging coordinates: XLOADS rows (ROWS_PER_PASS apart), one 16-byte piece
+    const bool stager = (STAGERS == NTHREADS) || wave < STAGERS / 64;
     const int x_row0 = tid / PIECES, x_piece = tid % PIECES;
     const uint32_t x_lds0 = G::X0 + (uint32_t)x_row0 * G::STRIDE + x_piece * 16;
 
@@ -334,6 +340,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         const int tok0 = (stream + j * S) * TM;
         const int k0 = seg * SEGMENT_ROWS;
         const int last = min(SEGMENT_ROWS, a.K - k0) - 1;
+        if (!stager) return;
         if (a.x_vec_ok && tok0 + TM <= a.M) {
             // fast path: K * ldx < 2 GiB (checked on the host), 32-bit offsets from a uniform base
             const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0;
@@ -352,6 +359,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     };
     // ---- ... and from registers into LDS buffer q % 2, as x - 128
     auto x_commit = [&](const int q, const int h) {
+        if (!stager) return;
         uint8_t* buf = lds + (q & 1) * G::BUF + x_lds0 + h * XH * ROWS_PER_PASS * G::STRIDE;
 #pragma unroll
         for (int u = 0; u < XH; ++u)
@@ -542,129 +550,6 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
             if (m0 < a.M) finish4<OUT, POST>(a, acc[r][i], s, bias, n, m0, lut);
         }
     }
-}
-
-// ---------------------------------------------------------------------------------------
-// host side: plan + dispatch
-// ---------------------------------------------------------------------------------------
-bool plan_supported(int token_tile, int variant)
-{
-    if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16;
-    if (token_tile == 64) return variant == 0 || variant == 8 || variant == 101 || variant == 102;
-    return false;
-}
-
-Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant)
-{
-    Plan p{};
-    p.max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? max_steps_per_segment : 8);
-    p.token_tile = force_tm ? force_tm : 128;
-    if (p.token_tile == 64 && variant > 100) {   // simple kernel
-        p.waves = 8;
-        p.row_tiles_per_wave = variant - 100;
-        p.simple = 1;
-        p.n_tok_tiles = (int)((M + 63) / 64);
-        p.n_row_groups = (ntiles + p.waves * p.row_tiles_per_wave - 1) / (p.waves * p.row_tiles_per_wave);
-        p.n_streams = 0;
-        p.xcd_map = 1;
-        p.workgroups = (int64_t)8 * p.n_row_groups * ((p.n_tok_tiles + 7) / 8);
-        return p;
-    }
-    p.row_tiles_per_wave = 1;
-    int wg_per_cu = 1;
-    if (p.token_tile == 128) {
-        // up to 4 steps per segment fit the 128-register budget of 16 waves; denser weights run
-        // with 8 waves (256 registers) and half as many rows per workgroup
-        p.waves = (p.max_steps <= 6) ? 16 : 8;
-        if (variant == 8) p.waves = 8;
-    } else {
-        p.waves = 8;      // 80 KB of LDS: two workgroups per CU
-        wg_per_cu = 2;
-    }
-    p.n_tok_tiles = (int)((M + p.token_tile - 1) / p.token_tile);
-    p.n_row_groups = (ntiles + p.waves - 1) / p.waves;
-    // S token-tile streams per row group, enough workgroups to fill every CU once
-    int S = (num_cus * wg_per_cu) / p.n_row_groups;
-    if (S < 1) S = 1;
-    if (S > p.n_tok_tiles) S = p.n_tok_tiles;
-    if (S >= 8) S -= S % 8;
-    p.n_streams = S;
-    p.xcd_map = (S % 8 == 0) ? 1 : 0;
-    p.workgroups = (int64_t)p.n_row_groups * S;
-    return p;
-}
-
-template <int TM, int NW, int MAXS>
-struct PipeLaunch {
-    template <int OUT, int POST>
-    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
-    {
-        hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST>), grid, block, 0, st, a);
-    }
-};
-
-template <int R>
-struct SimpleLaunch {
-    template <int OUT, int POST>
-    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
-    {
-        hipLaunchKernelGGL((spmm_rowtile_mfma_simple<64, 8, R, OUT, POST>), grid, block, 0, st, a);
-    }
-};
-
-template <class L>
-static void dispatch_epilogue(spmm_out_t out_type, spmm_postop_t postop, dim3 grid, dim3 block, hipStream_t st,
-                              const KernelArgs& a)
-{
-    const bool gelu = (postop == SPMM_POST_GELU);
-    switch (out_type) {
-    case SPMM_OUT_S32: L::template go<SPMM_OUT_S32, SPMM_POST_NONE>(grid, block, st, a); break;
-    case SPMM_OUT_F32:
-        if (gelu) L::template go<SPMM_OUT_F32, SPMM_POST_GELU>(grid, block, st, a);
-        else L::template go<SPMM_OUT_F32, SPMM_POST_NONE>(grid, block, st, a);
-        break;
-    case SPMM_OUT_S8:
-        if (gelu) L::template go<SPMM_OUT_S8, SPMM_POST_GELU>(grid, block, st, a);
-        else L::template go<SPMM_OUT_S8, SPMM_POST_NONE>(grid, block, st, a);
-        break;
-    case SPMM_OUT_U8:
-        if (gelu) L::template go<SPMM_OUT_U8, SPMM_POST_GELU>(grid, block, st, a);
-        else L::template go<SPMM_OUT_U8, SPMM_POST_NONE>(grid, block, st, a);
-        break;
-    }
-}
-
-int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_postop_t postop, void* stream)
-{
-    hipStream_t st = (hipStream_t)stream;
-    a.n_tok_tiles = plan.n_tok_tiles;
-    a.n_row_groups = plan.n_row_groups;
-    a.n_streams = plan.n_streams;
-    a.xcd_map = plan.xcd_map;
-    const dim3 grid((unsigned)plan.workgroups), block((unsigned)plan.waves * 64);
-    if (plan.simple) {
-        if (plan.row_tiles_per_wave == 1) dispatch_epilogue<SimpleLaunch<1>>(out_type, postop, grid, block, st, a);
-        else if (plan.row_tiles_per_wave == 2) dispatch_epilogue<SimpleLaunch<2>>(out_type, postop, grid, block, st, a);
-        else return (int)hipErrorInvalidValue;
-        return (int)hipGetLastError();
-    }
-    if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
-    const int key = plan.token_tile * 10000 + plan.waves * 100 + plan.max_steps;
-    switch (key) {
-    case 1281604: dispatch_epilogue<PipeLaunch<128, 16, 4>>(out_type, postop, grid, block, st, a); break;
-    case 1281605: dispatch_epilogue<PipeLaunch<128, 16, 5>>(out_type, postop, grid, block, st, a); break;
-    case 1281606: dispatch_epilogue<PipeLaunch<128, 16, 6>>(out_type, postop, grid, block, st, a); break;
-    case 1280804: dispatch_epilogue<PipeLaunch<128, 8, 4>>(out_type, postop, grid, block, st, a); break;
-    case 1280805: dispatch_epilogue<PipeLaunch<128, 8, 6>>(out_type, postop, grid, block, st, a); break;
-    case 1280806: dispatch_epilogue<PipeLaunch<128, 8, 6>>(out_type, postop, grid, block, st, a); break;
-    case 1280808: dispatch_epilogue<PipeLaunch<128, 8, 8>>(out_type, postop, grid, block, st, a); break;
-    case 640804: dispatch_epilogue<PipeLaunch<64, 8, 4>>(out_type, postop, grid, block, st, a); break;
-    case 640805: dispatch_epilogue<PipeLaunch<64, 8, 6>>(out_type, postop, grid, block, st, a); break;
-    case 640806: dispatch_epilogue<PipeLaunch<64, 8, 6>>(out_type, postop, grid, block, st, a); break;
-    case 640808: dispatch_epilogue<PipeLaunch<64, 8, 8>>(out_type, postop, grid, block, st, a); break;
-    default: return (int)hipErrorInvalidValue;
-    }
-    return (int)hipGetLastError();
 }
 
 }  // namespace spmm

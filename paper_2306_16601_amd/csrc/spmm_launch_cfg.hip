@@ -1,0 +1,70 @@
+// One kernel configuration of the SpMM kernels: this file is compiled once per configuration
+// (see build.py), so that the instantiations build in parallel.
+//   pipelined kernel : -DSPMM_CFG_TM=<128|96> -DSPMM_CFG_NW=<16|8> -DSPMM_CFG_MAXS=<4|5|6|8>
+//   simple kernel    : -DSPMM_CFG_SIMPLE=<1|2>      (row tiles per wave)
+// Each defines one function launch_cfg_<...>() that picks the epilogue instantiation and
+// launches it; spmm_plan.hip calls them.
+#include "spmm_kernels.h"
+
+namespace spmm {
+
+template <class L>
+static void dispatch_epilogue(spmm_out_t out_type, spmm_postop_t postop, dim3 grid, dim3 block, hipStream_t st,
+                              const KernelArgs& a)
+{
+    const bool gelu = (postop == SPMM_POST_GELU);
+    switch (out_type) {
+    case SPMM_OUT_S32: L::template go<SPMM_OUT_S32, SPMM_POST_NONE>(grid, block, st, a); break;
+    case SPMM_OUT_F32:
+        if (gelu) L::template go<SPMM_OUT_F32, SPMM_POST_GELU>(grid, block, st, a);
+        else L::template go<SPMM_OUT_F32, SPMM_POST_NONE>(grid, block, st, a);
+        break;
+    case SPMM_OUT_S8:
+        if (gelu) L::template go<SPMM_OUT_S8, SPMM_POST_GELU>(grid, block, st, a);
+        else L::template go<SPMM_OUT_S8, SPMM_POST_NONE>(grid, block, st, a);
+        break;
+    case SPMM_OUT_U8:
+        if (gelu) L::template go<SPMM_OUT_U8, SPMM_POST_GELU>(grid, block, st, a);
+        else L::template go<SPMM_OUT_U8, SPMM_POST_NONE>(grid, block, st, a);
+        break;
+    }
+}
+
+
+#define SPMM_CAT_(a, b) a##b
+#define SPMM_CAT(a, b) SPMM_CAT_(a, b)
+
+#ifdef SPMM_CFG_SIMPLE
+template <int R>
+struct SimpleLaunch {
+    template <int OUT, int POST>
+    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
+    {
+        hipLaunchKernelGGL((spmm_rowtile_mfma_simple<64, 8, R, OUT, POST>), grid, block, 0, st, a);
+    }
+};
+
+void SPMM_CAT(launch_cfg_simple_, SPMM_CFG_SIMPLE)(spmm_out_t out_type, spmm_postop_t postop, unsigned grid,
+                                                   unsigned block, void* stream, const KernelArgs& a)
+{
+    dispatch_epilogue<SimpleLaunch<SPMM_CFG_SIMPLE>>(out_type, postop, dim3(grid), dim3(block), (hipStream_t)stream, a);
+}
+#else
+template <int TM, int NW, int MAXS>
+struct PipeLaunch {
+    template <int OUT, int POST>
+    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
+    {
+        hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST>), grid, block, 0, st, a);
+    }
+};
+
+void SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(launch_cfg_, SPMM_CFG_TM), _), SPMM_CFG_NW), _), SPMM_CFG_MAXS)(
+    spmm_out_t out_type, spmm_postop_t postop, unsigned grid, unsigned block, void* stream, const KernelArgs& a)
+{
+    dispatch_epilogue<PipeLaunch<SPMM_CFG_TM, SPMM_CFG_NW, SPMM_CFG_MAXS>>(out_type, postop, dim3(grid), dim3(block),
+                                                                            (hipStream_t)stream, a);
+}
+#endif
+
+}  // namespace spmm

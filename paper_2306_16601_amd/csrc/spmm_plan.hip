@@ -1,0 +1,131 @@
+// Host side of the kernel launch: the plan (which configuration, which grid) and the dispatch
+// to the per-configuration launchers compiled from spmm_launch_cfg.hip.
+#include <hip/hip_runtime.h>
+
+#include "spmm_internal.h"
+
+namespace spmm {
+
+#define SPMM_DECLARE_CFG(name) \
+    void name(spmm_out_t, spmm_postop_t, unsigned grid, unsigned block, void* stream, const KernelArgs&)
+SPMM_DECLARE_CFG(launch_cfg_128_16_4);
+SPMM_DECLARE_CFG(launch_cfg_128_16_5);
+SPMM_DECLARE_CFG(launch_cfg_128_16_6);
+SPMM_DECLARE_CFG(launch_cfg_128_8_4);
+SPMM_DECLARE_CFG(launch_cfg_128_8_6);
+SPMM_DECLARE_CFG(launch_cfg_128_8_8);
+SPMM_DECLARE_CFG(launch_cfg_96_16_4);
+SPMM_DECLARE_CFG(launch_cfg_96_16_5);
+SPMM_DECLARE_CFG(launch_cfg_96_16_6);
+SPMM_DECLARE_CFG(launch_cfg_simple_1);
+SPMM_DECLARE_CFG(launch_cfg_simple_2);
+#undef SPMM_DECLARE_CFG
+
+bool plan_supported(int token_tile, int variant)
+{
+    if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16;
+    if (token_tile == 96) return variant == 0 || variant == 16;
+    if (token_tile == 64) return variant == 101 || variant == 102;
+    return false;
+}
+
+// Pipelined kernel: token tile tm, `waves` row tiles per workgroup.  S token-tile streams per
+// row group, enough workgroups to fill every CU once.
+static void fill_pipelined(Plan& p, int64_t M, int ntiles, int num_cus, int tm, int waves)
+{
+    p.token_tile = tm;
+    p.waves = waves;
+    p.row_tiles_per_wave = 1;
+    p.simple = 0;
+    p.n_tok_tiles = (int)((M + tm - 1) / tm);
+    p.n_row_groups = (ntiles + waves - 1) / waves;
+    int S = num_cus / p.n_row_groups;
+    if (S < 1) S = 1;
+    if (S > p.n_tok_tiles) S = p.n_tok_tiles;
+    if (S >= 8) S -= S % 8;
+    p.n_streams = S;
+    p.xcd_map = (S % 8 == 0) ? 1 : 0;
+    p.workgroups = (int64_t)p.n_row_groups * S;
+}
+
+// Relative duration of a plan: the longest stream's tokens (plus a start-up term, in tokens),
+// times the rounds needed when there are more workgroups than CUs.
+static double plan_cost(const Plan& p, int num_cus)
+{
+    const int per_stream = (p.n_tok_tiles + p.n_streams - 1) / p.n_streams;
+    const int64_t rounds = (p.workgroups + num_cus - 1) / num_cus;
+    return (double)rounds * ((double)per_stream * p.token_tile + 48.0);
+}
+
+Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant)
+{
+    Plan p{};
+    const int max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? max_steps_per_segment : 8);
+    p.max_steps = max_steps;
+    if (force_tm == 64) {   // simple kernel
+        p.token_tile = 64;
+        p.waves = 8;
+        p.row_tiles_per_wave = variant - 100;
+        p.simple = 1;
+        p.n_tok_tiles = (int)((M + 63) / 64);
+        p.n_row_groups = (ntiles + p.waves * p.row_tiles_per_wave - 1) / (p.waves * p.row_tiles_per_wave);
+        p.n_streams = 0;
+        p.xcd_map = 1;
+        p.workgroups = (int64_t)8 * p.n_row_groups * ((p.n_tok_tiles + 7) / 8);
+        return p;
+    }
+    // 16 waves have 128 registers each: at most 6 steps per segment; denser weights run with 8
+    // waves, 256 registers and half as many rows per workgroup (token tile 128 only).
+    if (max_steps > 6 || variant == 8) {
+        fill_pipelined(p, M, ntiles, num_cus, 128, 8);
+        return p;
+    }
+    if (force_tm) {
+        fill_pipelined(p, M, ntiles, num_cus, force_tm, 16);
+        return p;
+    }
+    // Token tile 128 or 96.  Measured on 6144 tokens: 96-token tiles cost more per token when the
+    // segments are short (the activation rows no longer fill cache lines, and the fixed work
+    // per tile weighs more), so they are used only from 5 steps per segment on, and there
+    // whenever they do not lengthen the longest stream.
+    fill_pipelined(p, M, ntiles, num_cus, 128, 16);
+    if (max_steps >= 5) {
+        Plan c{};
+        c.max_steps = max_steps;
+        fill_pipelined(c, M, ntiles, num_cus, 96, 16);
+        if (plan_cost(c, num_cus) <= plan_cost(p, num_cus)) p = c;
+    }
+    return p;
+}
+
+int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_postop_t postop, void* stream)
+{
+    a.n_tok_tiles = plan.n_tok_tiles;
+    a.n_row_groups = plan.n_row_groups;
+    a.n_streams = plan.n_streams;
+    a.xcd_map = plan.xcd_map;
+    const unsigned grid = (unsigned)plan.workgroups, block = (unsigned)plan.waves * 64;
+    if (plan.simple) {
+        if (plan.row_tiles_per_wave == 1) launch_cfg_simple_1(out_type, postop, grid, block, stream, a);
+        else if (plan.row_tiles_per_wave == 2) launch_cfg_simple_2(out_type, postop, grid, block, stream, a);
+        else return (int)hipErrorInvalidValue;
+        return (int)hipGetLastError();
+    }
+    if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
+    const int maxs = (plan.waves == 8 && plan.max_steps == 5) ? 6 : plan.max_steps;   // no 8-wave 5-step build
+    switch (plan.token_tile * 10000 + plan.waves * 100 + maxs) {
+    case 1281604: launch_cfg_128_16_4(out_type, postop, grid, block, stream, a); break;
+    case 1281605: launch_cfg_128_16_5(out_type, postop, grid, block, stream, a); break;
+    case 1281606: launch_cfg_128_16_6(out_type, postop, grid, block, stream, a); break;
+    case 1280804: launch_cfg_128_8_4(out_type, postop, grid, block, stream, a); break;
+    case 1280806: launch_cfg_128_8_6(out_type, postop, grid, block, stream, a); break;
+    case 1280808: launch_cfg_128_8_8(out_type, postop, grid, block, stream, a); break;
+    case 961604: launch_cfg_96_16_4(out_type, postop, grid, block, stream, a); break;
+    case 961605: launch_cfg_96_16_5(out_type, postop, grid, block, stream, a); break;
+    case 961606: launch_cfg_96_16_6(out_type, postop, grid, block, stream, a); break;
+    default: return (int)hipErrorInvalidValue;
+    }
+    return (int)hipGetLastError();
+}
+
+}  // namespace spmm

@@ -125,7 +125,7 @@ def test_config4_large_all_kernel_variants_agree_bitwise():
     case = wl.large_cases()[0]
     d = wl.make(case)
     a, _ = gpu_spmm(d["W"], d["X"], d, case)
-    for tuning in ((128, 0), (128, 8), (128, 16), (64, 0), (64, 101), (64, 102)):
+    for tuning in ((128, 0), (128, 8), (128, 16), (96, 0), (96, 16), (64, 101), (64, 102)):
         b, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=tuning)
         assert np.array_equal(a, b), tuning
 
@@ -151,7 +151,7 @@ def test_config5_grid_sample_s32_and_s8(case):
     (260, 100, 257), (5, 3000, 7),
 ])
 @pytest.mark.parametrize("out_type", ["s32", "s8"])
-@pytest.mark.parametrize("tuning", [None, (128, 0), (64, 0), (64, 102)], ids=["default", "tile128", "tile64", "simple"])
+@pytest.mark.parametrize("tuning", [None, (128, 16), (128, 8), (96, 16), (64, 102)], ids=["default", "tile128", "tile128w8", "tile96", "simple"])
 def test_ragged_shapes(N, K, M, out_type, tuning):
     case = wl.Case("ragged", N, K, M, 0.6, wl.N4K1, out_type, "none", keys=(60, N, K, M))
     check_case(case, tuning=tuning)
@@ -164,7 +164,7 @@ def test_many_token_tiles_and_segments(N, K, M, s):
     """Several token tiles per workgroup stream, 1 / 2 / 3+ K segments (resident and
     re-streamed weights), ragged last tile, every step-count variant of the kernel."""
     for ot, po in (("s32", "none"), ("s8", "gelu")):
-        for tuning in (None, (128, 0), (64, 0)):
+        for tuning in (None, (128, 0), (128, 8), (96, 0)):
             check_case(wl.Case("multi", N, K, M, s, wl.N4K1, ot, po, keys=(66, N, K, M)), tuning=tuning)
 
 

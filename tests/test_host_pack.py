@@ -160,7 +160,10 @@ def test_pack_argument_errors():
     assert L.spmm_set_tuning(hh, 48, 0) == sp.SPMM_E_UNSUPPORTED
     assert L.spmm_set_tuning(hh, 128, 101) == sp.SPMM_E_UNSUPPORTED
     assert L.spmm_set_tuning(hh, 0, 8) == sp.SPMM_E_ARG
+    assert L.spmm_set_tuning(hh, 64, 0) == sp.SPMM_E_UNSUPPORTED
     assert L.spmm_set_tuning(hh, 64, 102) == sp.SPMM_OK
+    assert L.spmm_set_tuning(hh, 96, 16) == sp.SPMM_OK
+    assert L.spmm_set_tuning(hh, 96, 8) == sp.SPMM_E_UNSUPPORTED
     assert L.spmm_set_tuning(hh, 0, 0) == sp.SPMM_OK
     sp.spmm_destroy(hh)
 
