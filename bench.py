@@ -59,6 +59,9 @@ def main() -> int:
     ap.add_argument("--tuning", default="", help="token_tile,variant override passed to spmm_set_tuning")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--only", default="", help="keep only the calls whose case name contains this substring")
+    ap.add_argument("--qkv", action="store_true",
+                    help="also time the three attention projections (N = K of the first shape) as three launches and "
+                         "as one launch of the stacked [3N, K] weight")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 256 MiB device copy (profiling aid: scales FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -214,6 +217,54 @@ def main() -> int:
             except Exception as exc:   # the comparator is context only
                 dense["%dx%d" % (N, K)] = {"error": repr(exc)[:120]}
 
+    # ------------------------------------------------------------------ Q, K, V projections sharing one X: three launches
+    # against one launch of the stacked weight (same outputs, see tests)
+    qkv = None
+    if args.qkv:
+        c0 = calls[0]
+        case0 = c0["case"]
+        parts = [wl.make(case0.with_(keys=(case0.keys + (i,)))) for i in range(3)]
+        hs = [sp.spmm_pack(p["W"], case0.orientation) for p in parts]
+        hb = sp.spmm_pack(np.concatenate([p["W"] for p in parts]), case0.orientation)
+        ws3 = torch.from_numpy(np.concatenate([p["w_scale"] for p in parts])).cuda()
+        b3 = torch.from_numpy(np.concatenate([p["bias"] for p in parts])).cuda()
+        N0, M0 = c0["N"], c0["M"]
+        eps = [sp.make_epilogue(ws3[i * N0:(i + 1) * N0], c0["d"]["x_scale"], 0, b3[i * N0:(i + 1) * N0], case0.postop,
+                                case0.out_type, c0["d"]["out_scale"], 0, c0["d"]["mid_scale"], c0["keep"][2])
+               for i in range(3)]
+        epb = sp.make_epilogue(ws3, c0["d"]["x_scale"], 0, b3, case0.postop, case0.out_type, c0["d"]["out_scale"], 0,
+                               c0["d"]["mid_scale"], c0["keep"][2])
+        o3 = [torch.empty((3 * N0, M0), dtype=tdt[case0.out_type], device="cuda") for _ in range(ROTATE)]
+        ob = [torch.empty((3 * N0, M0), dtype=tdt[case0.out_type], device="cuda") for _ in range(ROTATE)]
+        st = torch.cuda.current_stream().cuda_stream
+
+        def three(it):
+            j = it % ROTATE
+            for i in range(3):
+                sp.spmm_run(hs[i], c0["Xs"][j], M0, M0, eps[i], o3[j][i * N0:(i + 1) * N0], M0, st)
+
+        def one(it):
+            j = it % ROTATE
+            sp.spmm_run(hb, c0["Xs"][j], M0, M0, epb, ob[j], M0, st)
+
+        res = {}
+        for name, fn in (("three_launches_us", three), ("stacked_launch_us", one)):
+            for it in range(6):
+                fn(it)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for it in range(30):
+                fn(it)
+            e1.record()
+            torch.cuda.synchronize()
+            res[name] = round(e0.elapsed_time(e1) * 1e3 / 30, 2)
+        res["identical_outputs"] = bool(torch.equal(o3[0], ob[0]))
+        res["shape"] = "3 x %dx%d, M=%d, %s" % (N0, c0["K"], M0, case0.name)
+        qkv = res
+        for h in hs + [hb]:
+            sp.spmm_destroy(h)
+
     # ------------------------------------------------------------------ per-shape rows + roofline of the SpMM kernel
     rows = []
     for ci, c in enumerate(calls):
@@ -296,7 +347,7 @@ def main() -> int:
         "config": {"workload": wname, "calls_per_step": nc, "tokens": calls[0]["M"], "orientation": "n4k1",
                    "buffer_rotation": ROTATE},
         "nonzero_tops": round(nnz_tops, 2),
-        "roofline": roofline, "cpu_baseline": cpu, "dense_int8_gemm": dense, "per_call": rows,
+        "roofline": roofline, "cpu_baseline": cpu, "dense_int8_gemm": dense, "qkv_stacked": qkv, "per_call": rows,
         "ms_per_step_eager_with_events": round(eager_ms_per_step, 5),
         "ms_per_step_graph": (round(graph_ms_per_step, 5) if graph_ms_per_step is not None else None),
         "launch_mode": ("hip_graph_replay" if graph_ms_per_step is not None else "eager"),

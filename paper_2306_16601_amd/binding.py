@@ -216,6 +216,7 @@ def make_epilogue(w_scale=None, x_scale: float = 1.0, x_zero_point: int = 0, bia
     ep.out_zero_point = int(out_zero_point)
     ep.mid_scale = float(np.float32(mid_scale))
     ep.lut = _dev_ptr(lut)
+    ep._keepalive = (w_scale, bias, lut)   # the struct holds raw addresses: keep their owners alive with it
     return ep
 
 

@@ -130,6 +130,65 @@ def test_config4_large_all_kernel_variants_agree_bitwise():
         assert np.array_equal(a, b), tuning
 
 
+# ---------------------------------------------------------------------------- beyond the five configs
+def _run_with_table(d, case, table):
+    """spmm_run with a caller-built 256-entry table in place of the GELU one."""
+    h = sp.spmm_pack(d["W"], case.orientation)
+    try:
+        out = torch.empty((case.N, case.M), dtype=TORCH_DT[case.out_type], device="cuda")
+        w_scale, bias, lut, X = dev(d["w_scale"]), dev(d["bias"]), dev(table), dev(d["X"])   # alive until the sync
+        ep = sp.make_epilogue(w_scale, d["x_scale"], d["x_zero_point"], bias, "gelu",
+                              case.out_type, d["out_scale"], d["out_zero_point"], d["mid_scale"], lut)
+        sp.spmm_run(h, X, case.M, case.M, ep, out, case.M, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+    finally:
+        sp.spmm_destroy(h)
+
+
+@pytest.mark.parametrize("out_type", ["s8", "u8"])
+def test_table_of_any_elementwise_chain(out_type):
+    # Algorithm 2 holds for every element-wise chain with a low-precision input: the library only
+    # looks the key up, so a table of some other chain (here tanh -> requantise, and a random
+    # permutation) must come out exactly as the oracle's look-up of the same table.
+    case = wl.Case("table", 80, 300, 333, 0.8, wl.N4K1, out_type, "gelu", keys=(91, 80, 300, 333))
+    d = wl.make(case)
+    keys = np.arange(-128, 128, dtype=np.float64)
+    lo, hi = (0, 255) if out_type == "u8" else (-128, 127)
+    tanh_q = np.clip(np.rint(np.tanh(keys * float(d["mid_scale"])) * 100.0) + (128 if out_type == "u8" else 0), lo, hi)
+    perm = wl.rng_for(92, 7).permutation(256) + lo
+    for table in (tanh_q, perm):
+        table = table.astype(np.uint8 if out_type == "u8" else np.int8)
+        got = _run_with_table(d, case, table.view(np.int8))
+        ref = oracle.spmm(d["W"], d["X"], d["w_scale"], d["x_scale"], d["bias"], "gelu", out_type, d["out_scale"],
+                          d["out_zero_point"], d["mid_scale"], d["x_zero_point"], lut=table)
+        assert np.array_equal(got, ref)
+        assert len(np.unique(got)) > 8      # the table is really exercised
+
+
+def test_stacked_qkv_is_three_projections():
+    # Q, K and V share one X (Figure 3(a)): packing the three weights as one [3N, K] matrix gives
+    # one launch whose output is the three separate outputs stacked, bit for bit.
+    N, K, M = 256, 256, 640
+    cases = [wl.Case("qkv%d" % i, N, K, M, 0.85, wl.N4K1, "s8", "none", keys=(93, i)) for i in range(3)]
+    ds = [wl.make(c) for c in cases]
+    X = ds[0]["X"]
+    sep = []
+    for c, d in zip(cases, ds):
+        d = dict(d, X=X, out_scale=ds[0]["out_scale"], x_scale=ds[0]["x_scale"])
+        out, ok = gpu_spmm(d["W"], X, d, c)
+        assert ok
+        ref = oracle_spmm(d["W"], X, d, c)
+        assert np.array_equal(out, ref)
+        sep.append(out)
+    stacked = dict(ds[0], W=np.concatenate([d["W"] for d in ds]), X=X,
+                   w_scale=np.concatenate([d["w_scale"] for d in ds]), bias=np.concatenate([d["bias"] for d in ds]))
+    big = wl.Case("qkv", 3 * N, K, M, 0.85, wl.N4K1, "s8", "none", keys=(93,))
+    out, ok = gpu_spmm(stacked["W"], X, stacked, big)
+    assert ok
+    assert np.array_equal(out, np.concatenate(sep))
+
+
 # ---------------------------------------------------------------------------- config 5 (sample of the grid)
 def _grid_sample():
     allc = wl.grid_cases(out_type="s32")
