@@ -35,6 +35,9 @@ def load(path: str) -> ctypes.CDLL:
     L.oracle_epilogue.restype = ctypes.c_int
     L.oracle_epilogue.argtypes = [vp, i64, i64, vp, f32, vp, ctypes.c_int, ctypes.c_int,
                                   f32, i32, f32, vp, vp, i64]
+    L.oracle_epilogue_sum.restype = ctypes.c_int
+    L.oracle_epilogue_sum.argtypes = [vp, i64, i64, vp, f32, vp, ctypes.c_int, vp, i64, ctypes.c_int,
+                                      f32, i32, f32, vp, vp, i64]
     L.oracle_num_threads.restype = ctypes.c_int
     L.oracle_set_num_threads.argtypes = [ctypes.c_int]
     return L
@@ -92,8 +95,9 @@ def gelu_lut(mid_scale: float, out_scale: float, out_zero_point: int = 0,
 def epilogue(acc: np.ndarray, w_scale: Optional[np.ndarray], x_scale: float = 1.0,
              bias: Optional[np.ndarray] = None, postop: str = "none", out_type: str = "s32",
              out_scale: float = 1.0, out_zero_point: int = 0, mid_scale: float = 1.0,
-             lut: Optional[np.ndarray] = None) -> np.ndarray:
-    """Post-operator chain applied to an int32 accumulator matrix."""
+             lut: Optional[np.ndarray] = None, sum: Optional[np.ndarray] = None) -> np.ndarray:
+    """Post-operator chain applied to an int32 accumulator matrix; `sum` is the optional second
+    operand of the Sum post-operator, fp32 [N, M]."""
     assert acc.dtype == np.int32 and acc.flags.c_contiguous
     N, M = acc.shape
     if w_scale is not None:
@@ -105,11 +109,14 @@ def epilogue(acc: np.ndarray, w_scale: Optional[np.ndarray], x_scale: float = 1.
     if lut is not None:
         lut = np.ascontiguousarray(lut).view(np.int8)
         assert lut.shape == (256,)
+    if sum is not None:
+        sum = np.ascontiguousarray(sum, dtype=np.float32)
+        assert sum.shape == (N, M)
     out = np.empty((N, M), dtype=_OUT_DTYPES[out_type])
-    rc = lib().oracle_epilogue(_ptr(acc), N, M, _ptr(w_scale), float(np.float32(x_scale)),
-                               _ptr(bias), POSTOPS[postop], OUT_TYPES[out_type],
-                               float(np.float32(out_scale)), int(out_zero_point),
-                               float(np.float32(mid_scale)), _ptr(lut), _ptr(out), M)
+    rc = lib().oracle_epilogue_sum(_ptr(acc), N, M, _ptr(w_scale), float(np.float32(x_scale)),
+                                   _ptr(bias), POSTOPS[postop], _ptr(sum), M, OUT_TYPES[out_type],
+                                   float(np.float32(out_scale)), int(out_zero_point),
+                                   float(np.float32(mid_scale)), _ptr(lut), _ptr(out), M)
     if rc != 0:
         raise ValueError("oracle_epilogue: invalid argument combination")
     return out
@@ -119,7 +126,7 @@ def spmm(W: np.ndarray, X: np.ndarray, w_scale: Optional[np.ndarray] = None,
          x_scale: float = 1.0, bias: Optional[np.ndarray] = None, postop: str = "none",
          out_type: str = "s32", out_scale: float = 1.0, out_zero_point: int = 0,
          mid_scale: float = 1.0, x_zero_point: int = 0,
-         lut: Optional[np.ndarray] = None) -> np.ndarray:
+         lut: Optional[np.ndarray] = None, sum: Optional[np.ndarray] = None) -> np.ndarray:
     """out = epilogue(W . X) on the dense-with-zeros W.  For GELU with an int8
     output the lookup table is built here unless one is passed."""
     acc = acc_s32(W, X, x_zero_point)
@@ -128,4 +135,4 @@ def spmm(W: np.ndarray, X: np.ndarray, w_scale: Optional[np.ndarray] = None,
     if postop == "gelu" and out_type in ("s8", "u8") and lut is None:
         lut = gelu_lut(mid_scale, out_scale, out_zero_point, out_type)
     return epilogue(acc, w_scale, x_scale, bias, postop, out_type, out_scale,
-                    out_zero_point, mid_scale, lut)
+                    out_zero_point, mid_scale, lut, sum)

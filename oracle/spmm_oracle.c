@@ -23,6 +23,10 @@
  *   GELU, f32 out :  z = (float)(0.5 * y * erfc(-y / sqrt(2)))   evaluated in double
  *   GELU, int8 out:  t = sat_s8(rintf(y * (1.0f / mid_scale)));  q = lut[t + 128]
  *   no post-op    :  z = y
+ *   Sum (optional):  z = z + R[n][m]       one binary32 add of a second [N][M] tensor
+ *                    (Figure 3 names Sum among the fused post-operators without a formula;
+ *                    reading: the residual is added after BiasAdd / GeLU and before Quantize.
+ *                    Not combined with the table chain, whose value is a function of one key.)
  *   Quantize      :  q = (int) min(hi, max(lo, rintf(z * (1.0f / out_scale)) + (float)out_zp))
  * rintf / rint round half to even (default rounding mode).
  *
@@ -92,17 +96,20 @@ int oracle_gelu_lut(float mid_scale, float out_scale, int32_t out_zp, int out_ty
 
 /* Post-operator chain on an int32 accumulator matrix acc [N][M] (ld = M).
  * out is [N][ldo] of the element type selected by out_type.
+ * sum: optional second operand of the Sum post-operator, [N][ld_sum] binary32, or NULL.
  * Returns 0, or -1 for an invalid combination. */
-int oracle_epilogue(const int32_t *acc, int64_t N, int64_t M,
-                    const float *w_scale, float x_scale, const float *bias,
-                    int postop, int out_type, float out_scale, int32_t out_zp,
-                    float mid_scale, const int8_t *lut, void *out, int64_t ldo)
+int oracle_epilogue_sum(const int32_t *acc, int64_t N, int64_t M,
+                        const float *w_scale, float x_scale, const float *bias,
+                        int postop, const float *sum, int64_t ld_sum,
+                        int out_type, float out_scale, int32_t out_zp,
+                        float mid_scale, const int8_t *lut, void *out, int64_t ldo)
 {
     if (out_type < ORACLE_OUT_S32 || out_type > ORACLE_OUT_U8) return -1;
     if (postop != ORACLE_POST_NONE && postop != ORACLE_POST_GELU) return -1;
     const int quant = (out_type == ORACLE_OUT_S8 || out_type == ORACLE_OUT_U8);
     if (out_type != ORACLE_OUT_S32 && !w_scale) return -1;
     if (postop == ORACLE_POST_GELU && quant && !lut) return -1;
+    if (sum && (out_type == ORACLE_OUT_S32 || (postop == ORACLE_POST_GELU && quant))) return -1;
 
     const float lo = (out_type == ORACLE_OUT_U8) ? 0.0f : -128.0f;
     const float hi = (out_type == ORACLE_OUT_U8) ? 255.0f : 127.0f;
@@ -124,6 +131,8 @@ int oracle_epilogue(const int32_t *acc, int64_t N, int64_t M,
                 float z = y;
                 if (postop == ORACLE_POST_GELU)
                     z = (float)oracle_gelu((double)y);
+                if (sum)
+                    z = z + sum[n * ld_sum + m];
                 ((float *)out)[n * ldo + m] = z;
                 continue;
             }
@@ -132,7 +141,10 @@ int oracle_epilogue(const int32_t *acc, int64_t N, int64_t M,
                 const int t = (int)sat_round(rintf(y * inv_mid), -128.0f, 127.0f);
                 q = (out_type == ORACLE_OUT_U8) ? (int)(uint8_t)lut[t + 128] : (int)lut[t + 128];
             } else {
-                q = (int)sat_round(rintf(y * inv_out) + (float)out_zp, lo, hi);
+                float z = y;
+                if (sum)
+                    z = z + sum[n * ld_sum + m];
+                q = (int)sat_round(rintf(z * inv_out) + (float)out_zp, lo, hi);
             }
             if (out_type == ORACLE_OUT_S8)
                 ((int8_t *)out)[n * ldo + m] = (int8_t)q;
@@ -141,6 +153,16 @@ int oracle_epilogue(const int32_t *acc, int64_t N, int64_t M,
         }
     }
     return 0;
+}
+
+/* The chain without Sum. */
+int oracle_epilogue(const int32_t *acc, int64_t N, int64_t M,
+                    const float *w_scale, float x_scale, const float *bias,
+                    int postop, int out_type, float out_scale, int32_t out_zp,
+                    float mid_scale, const int8_t *lut, void *out, int64_t ldo)
+{
+    return oracle_epilogue_sum(acc, N, M, w_scale, x_scale, bias, postop, NULL, 0, out_type, out_scale, out_zp,
+                               mid_scale, lut, out, ldo);
 }
 
 /* Threads an OpenMP parallel region of this library uses (reported beside timings). */

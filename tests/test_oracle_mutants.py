@@ -25,7 +25,7 @@ MUTANTS = [
      [pins.test_dequant_bias_is_single_rounding_fma]),
     ("bias_dropped", "const float b = bias ? bias[n] : 0.0f;", "const float b = 0.0f;",
      [pins.test_rounding_pins_fixture]),
-    ("round_half_away", "rintf(y * inv_out)", "roundf(y * inv_out)",
+    ("round_half_away", "rintf(z * inv_out)", "roundf(z * inv_out)",
      [pins.test_rounding_pins_fixture]),
     ("zero_point_dropped", "+ (float)out_zp, lo, hi)", ", lo, hi)",
      [pins.test_rounding_pins_fixture]),
@@ -45,6 +45,32 @@ MUTANTS = [
      [pins.test_gelu_int8_path_is_quantise_then_table]),
     ("scale_not_per_channel", "? w_scale[n] * x_scale :", "? w_scale[0] * x_scale :",
      [pins.test_dequant_bias_is_single_rounding_fma]),
+    ("sum_before_gelu", """                float z = y;
+                if (postop == ORACLE_POST_GELU)
+                    z = (float)oracle_gelu((double)y);
+                if (sum)
+                    z = z + sum[n * ld_sum + m];""", """                float z = y;
+                if (sum)
+                    z = z + sum[n * ld_sum + m];
+                if (postop == ORACLE_POST_GELU)
+                    z = (float)oracle_gelu((double)z);""",
+     [pins.test_sum_comes_after_gelu]),
+    ("sum_transposed", """                    z = z + sum[n * ld_sum + m];
+                ((float *)out)""", """                    z = z + sum[(m % N) * ld_sum + (n % M)];
+                ((float *)out)""",
+     [pins.test_sum_is_one_rounded_add_after_bias]),
+    ("sum_added_in_double", """                    z = z + sum[n * ld_sum + m];
+                ((float *)out)""", """                    z = (float)((double)a * (double)s + (double)b + (double)sum[n * ld_sum + m]);
+                ((float *)out)""",
+     [pins.test_sum_is_one_rounded_add_after_bias]),
+    ("sum_after_quantize_scale", """                    z = z + sum[n * ld_sum + m];
+                q = (int)sat_round(rintf(z * inv_out)""", """                    z = z + sum[n * ld_sum + m] * out_scale;
+                q = (int)sat_round(rintf(z * inv_out)""",
+     [lambda: pins.test_sum_comes_before_quantize("s8", -128, 127)]),
+    ("sum_dropped_when_quantizing", """                if (sum)
+                    z = z + sum[n * ld_sum + m];
+                q = (int)sat_round""", """                q = (int)sat_round""",
+     [lambda: pins.test_sum_comes_before_quantize("u8", 0, 255)]),
 ]
 
 

@@ -396,3 +396,89 @@ def test_invalid_combinations_raise():
         oracle.epilogue(acc, None, 1.0, None, "none", "f32")
     with pytest.raises(ValueError):
         oracle.epilogue(acc, np.ones(2, np.float32), 1.0, None, "gelu", "s8", 1.0, 0, 1.0, None)
+
+
+# ----------------------------------------------------------------------------
+# Sum post-operator (Figure 3): a second [N, M] binary32 tensor added after BiasAdd / GeLU and
+# before Quantize, one correctly rounded binary32 add
+# ----------------------------------------------------------------------------
+def _sum_inputs(seed=31, N=24, M=19):
+    rng = np.random.default_rng(seed)
+    acc = rng.integers(-2_000_000, 2_000_000, size=(N, M), dtype=np.int32)
+    w_scale = rng.uniform(1e-3, 1e-2, size=N).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    R = (rng.standard_normal((N, M)) * 37.0).astype(np.float32)
+    return acc, w_scale, bias, R
+
+
+def test_sum_is_one_rounded_add_after_bias():
+    acc, w_scale, bias, R = _sum_inputs()
+    y = oracle.epilogue(acc, w_scale, 0.02, bias, "none", "f32")          # pinned above
+    got = oracle.epilogue(acc, w_scale, 0.02, bias, "none", "f32", sum=R)
+    n_inexact = 0
+    for n in range(acc.shape[0]):
+        for m in range(acc.shape[1]):
+            exact = Fraction(float(y[n, m])) + Fraction(float(R[n, m]))
+            assert float(got[n, m]) == f32_round(exact), (n, m)
+            n_inexact += int(Fraction(float(got[n, m])) != exact)
+    assert n_inexact > 0                       # the add really rounds somewhere in the sample
+    # the residual is indexed [n][m]: a transposed read would change this asymmetric case
+    acc2 = np.zeros((2, 3), np.int32)
+    R2 = np.arange(6, dtype=np.float32).reshape(2, 3)
+    out = oracle.epilogue(acc2, np.ones(2, np.float32), 1.0, None, "none", "f32", sum=R2)
+    assert np.array_equal(out, R2)
+
+
+def test_sum_of_zeros_changes_nothing():
+    acc, w_scale, bias, R = _sum_inputs(32)
+    Z = np.zeros_like(R)
+    for post, ot in (("none", "f32"), ("gelu", "f32"), ("none", "s8"), ("none", "u8")):
+        a = oracle.epilogue(acc, w_scale, 0.02, bias, post, ot, 0.11, 3)
+        b = oracle.epilogue(acc, w_scale, 0.02, bias, post, ot, 0.11, 3, sum=Z)
+        assert np.array_equal(a, b), (post, ot)      # (by value: -0.0 + 0.0 is +0.0)
+
+
+def test_sum_comes_after_gelu():
+    mpmath = pytest.importorskip("mpmath")
+    acc, w_scale, bias, R = _sum_inputs(33)
+    g = oracle.epilogue(acc, w_scale, 0.002, bias, "gelu", "f32")          # pinned above
+    got = oracle.epilogue(acc, w_scale, 0.002, bias, "gelu", "f32", sum=R)
+    y = oracle.epilogue(acc, w_scale, 0.002, bias, "none", "f32")
+    differs_from_wrong_order = 0
+    for n in range(acc.shape[0]):
+        for m in range(acc.shape[1]):
+            assert float(got[n, m]) == f32_round(Fraction(float(g[n, m])) + Fraction(float(R[n, m])))
+            x = mpmath.mpf(float(y[n, m])) + mpmath.mpf(float(R[n, m]))
+            wrong = 0.5 * x * mpmath.erfc(-x / mpmath.sqrt(2))              # GELU(y + r)
+            differs_from_wrong_order += int(abs(float(wrong) - float(got[n, m])) > 1e-3)
+    assert differs_from_wrong_order > 100
+
+
+@pytest.mark.parametrize("out_type,lo,hi", [("s8", -128, 127), ("u8", 0, 255)])
+def test_sum_comes_before_quantize(out_type, lo, hi):
+    acc, w_scale, bias, R = _sum_inputs(34)
+    R = (R / 8).astype(np.float32)
+    out_scale, zp = np.float32(0.173), 7
+    z = oracle.epilogue(acc, w_scale, 0.002, bias, "none", "f32", sum=R)   # pinned above
+    got = oracle.epilogue(acc, w_scale, 0.002, bias, "none", out_type, out_scale, zp, sum=R)
+    inv = np.float32(1.0) / out_scale
+    for n in range(acc.shape[0]):
+        for m in range(acc.shape[1]):
+            t = f32_round(Fraction(float(z[n, m])) * Fraction(float(inv)))
+            assert int(got[n, m]) == min(hi, max(lo, py_round_half_even(t) + zp))
+    assert len(np.unique(got)) > 20 and np.mean((got == lo) | (got == hi)) < 0.6   # not all saturated
+    # an exact tie after the add: (0.5 + 2.0) / 1.0 = 2.5 -> 2, (1.5 + 2.0) -> 4  (half to even)
+    a = np.array([[1, 3]], np.int32)
+    r = np.array([[2.0, 2.0]], np.float32)
+    q = oracle.epilogue(a, np.array([0.5], np.float32), 1.0, None, "none", out_type, 1.0, 0, sum=r)
+    assert q.tolist() == [[2, 4]]
+
+
+def test_sum_invalid_combinations_raise():
+    acc = np.zeros((2, 2), np.int32)
+    R = np.zeros((2, 2), np.float32)
+    lut = np.zeros(256, np.int8)
+    with pytest.raises(ValueError):      # a table entry is a function of one key: no second operand
+        oracle.epilogue(acc, np.ones(2, np.float32), 1.0, None, "gelu", "s8", 1.0, 0, 1.0, lut, sum=R)
+    with pytest.raises(ValueError):      # raw accumulators take no post-operators
+        oracle.epilogue(acc, np.ones(2, np.float32), 1.0, None, "none", "s32", sum=R)
