@@ -53,7 +53,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="large", choices=["large", "base", "mini"])
+    ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "large_sum"],
+                    help="large_sum: the two BERT-Large Linears that feed a residual add (attention output and "
+                         "second feed-forward), with the Sum post-operator and fp32 output")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--tuning", default="", help="token_tile,variant override passed to spmm_set_tuning")
@@ -89,6 +91,9 @@ def main() -> int:
     elif args.workload == "base":
         cases = [c for c in wl.base_cases(batches=(32,), sparsities=(0.9, 0.8))]
         wname = "bert_base_layers_m4096_s90_s80_f32"
+    elif args.workload == "large_sum":
+        cases = [c.with_(out_type="f32", postop="none") for c in wl.large_cases() if c.N == 1024]
+        wname = "bert_large_residual_linears_m6144_s90_s80_sum_f32"
     else:
         cases = wl.mini_cases()
         wname = "bert_mini_ffn_pair_m1024_s80"
@@ -115,19 +120,30 @@ def main() -> int:
         lut = None
         if case.postop == "gelu" and case.out_type in ("s8", "u8"):
             lut = torch.from_numpy(sp.spmm_make_gelu_lut(d["mid_scale"], d["out_scale"], 0, case.out_type)).cuda()
-        ep = sp.make_epilogue(ws, d["x_scale"], 0, bias, case.postop, case.out_type, d["out_scale"], 0,
-                              d["mid_scale"], lut)
+        Rs = None
+        if args.workload == "large_sum":
+            R = (wl.rng_for(97, case.N, case.M).standard_normal((case.N, case.M)) *
+                 wl.preact_sigma(case.K, case.sparsity)).astype(np.float32)
+            d["R"] = R
+            Rs = [torch.from_numpy(R).cuda() for _ in range(ROTATE)]
+            eps = [sp.make_epilogue(ws, d["x_scale"], 0, bias, case.postop, case.out_type, d["out_scale"], 0,
+                                    d["mid_scale"], lut, Rs[j], case.M) for j in range(ROTATE)]
+        else:
+            eps = [sp.make_epilogue(ws, d["x_scale"], 0, bias, case.postop, case.out_type, d["out_scale"], 0,
+                                    d["mid_scale"], lut)] * ROTATE
+        ep = eps[0]
         Xs = [torch.from_numpy(d["X"]).cuda() for _ in range(ROTATE)]
         outs = [torch.empty((N, case.M), dtype=tdt[case.out_type], device="cuda") for _ in range(ROTATE)]
-        calls.append(dict(case=case, d=d, h=h, ep=ep, keep=(ws, bias, lut), Xs=Xs, outs=outs, N=N, K=K,
+        calls.append(dict(case=case, d=d, h=h, ep=ep, eps=eps, keep=(ws, bias, lut, Rs), Xs=Xs, outs=outs, N=N, K=K,
                           M=case.M, nnzb=nnzb, padded=padded, dev_bytes=dev_bytes,
-                          bytes=algorithmic_bytes(N, K, case.M, nnzb, out_elem[case.out_type]),
+                          bytes=algorithmic_bytes(N, K, case.M, nnzb, out_elem[case.out_type]) +
+                          (4 * N * case.M if Rs else 0),
                           dense_ops=2.0 * N * K * case.M, nnz_ops=2.0 * 4 * nnzb * case.M,
                           plan=sp.spmm_plan(h, case.M, case.out_type)))
 
     def launch(c, it):
         j = it % ROTATE
-        sp.spmm_run(c["h"], c["Xs"][j], c["M"], c["M"], c["ep"], c["outs"][j], c["M"],
+        sp.spmm_run(c["h"], c["Xs"][j], c["M"], c["M"], c["eps"][j], c["outs"][j], c["M"],
                     torch.cuda.current_stream().cuda_stream)
 
     if args.calibrate_copy:
@@ -323,7 +339,7 @@ def main() -> int:
             got = c["outs"][0].cpu().numpy()
             t1 = time.perf_counter()
             ref = oracle.spmm(d["W"], d["X"], d["w_scale"], d["x_scale"], d["bias"], case.postop, case.out_type,
-                              d["out_scale"], 0, d["mid_scale"])
+                              d["out_scale"], 0, d["mid_scale"], sum=d.get("R"))
             secs += time.perf_counter() - t1
             ops += c["dense_ops"]
             if case.out_type == "f32" and case.postop == "gelu":

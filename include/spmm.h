@@ -63,6 +63,10 @@ typedef enum {
  *   acc = sum_k W[n][k] * (X[k][m] - x_zero_point)                          (int32)
  *   y   = fmaf((float)acc, w_scale[n] * x_scale, bias ? bias[n] : 0)         (binary32)
  *   POST_NONE: z = y        POST_GELU, F32 out: z = y * Phi(y)  (erf form)
+ *   Sum (Figure 3), when `sum` is given: z = z + sum[n][m], one binary32 add of a second
+ *            tensor of the output's shape (the residual), after BiasAdd / GeLU and before
+ *            Quantize.  Not available with S32 output, nor with the table chain
+ *            (GELU + S8/U8), whose value is a function of one key: SPMM_E_UNSUPPORTED.
  *   S8/U8 out without GELU: q = sat(rint(z * (1/out_scale)) + out_zero_point)
  *   S8/U8 out with GELU   : t = sat_s8(rint(y * (1/mid_scale)));  q = lut[t + 128]
  * rint is round-half-to-even; 1/scale is one binary32 division done on the host.
@@ -78,6 +82,8 @@ typedef struct {
     int32_t out_zero_point; /* S8/U8 without GELU                                        */
     float mid_scale;        /* GELU + S8/U8: scale of the pre-activation code (> 0)      */
     const int8_t *lut;      /* GELU + S8/U8: device [256] table from spmm_make_gelu_lut  */
+    const float *sum;       /* device [N][ld_sum] binary32 or NULL: operand of Sum       */
+    int64_t ld_sum;         /* >= M when sum is given (in elements)                       */
 } spmm_epilogue_t;
 
 /* Compress a weight matrix (Section 3.2: the kernel is specialised on the sparse weight
@@ -138,7 +144,8 @@ spmm_status_t spmm_layout_export(const spmm_handle_t *h, uint8_t *vals_host, uin
  *   M > 0
  * Must be called with the handle's device current.
  * Errors: SPMM_E_ARG (also: missing w_scale / lut, non-positive scales, zero point out
- * of range), SPMM_E_DEVICE. */
+ * of range, ld_sum < M), SPMM_E_UNSUPPORTED (Sum with S32 output or with the table chain),
+ * SPMM_E_DEVICE. */
 spmm_status_t spmm_run(const spmm_handle_t *h, const uint8_t *X_dev, int64_t M, int64_t ldx,
                        const spmm_epilogue_t *ep, void *out_dev, int64_t ldo, void *hip_stream);
 

@@ -45,6 +45,8 @@ class spmm_epilogue_t(ctypes.Structure):
         ("out_zero_point", ctypes.c_int32),
         ("mid_scale", ctypes.c_float),
         ("lut", ctypes.c_void_p),
+        ("sum", ctypes.c_void_p),
+        ("ld_sum", ctypes.c_int64),
     ]
 
 
@@ -204,7 +206,7 @@ def spmm_set_tuning(handle: int, token_tile: int = 0, variant: int = 0) -> None:
 
 def make_epilogue(w_scale=None, x_scale: float = 1.0, x_zero_point: int = 0, bias=None, postop="none",
                   out_type="s32", out_scale: float = 1.0, out_zero_point: int = 0, mid_scale: float = 1.0,
-                  lut=None) -> spmm_epilogue_t:
+                  lut=None, sum=None, ld_sum: int = 0) -> spmm_epilogue_t:
     ep = spmm_epilogue_t()
     ep.w_scale = _dev_ptr(w_scale)
     ep.x_scale = float(np.float32(x_scale))
@@ -216,7 +218,9 @@ def make_epilogue(w_scale=None, x_scale: float = 1.0, x_zero_point: int = 0, bia
     ep.out_zero_point = int(out_zero_point)
     ep.mid_scale = float(np.float32(mid_scale))
     ep.lut = _dev_ptr(lut)
-    ep._keepalive = (w_scale, bias, lut)   # the struct holds raw addresses: keep their owners alive with it
+    ep.sum = _dev_ptr(sum)
+    ep.ld_sum = int(ld_sum)
+    ep._keepalive = (w_scale, bias, lut, sum)   # the struct holds raw addresses: keep their owners alive with it
     return ep
 
 

@@ -200,6 +200,10 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
         if (!ep->w_scale) return SPMM_E_ARG;
         if (!(ep->x_scale == ep->x_scale)) return SPMM_E_ARG;   // NaN
     }
+    if (ep->sum) {
+        if (ep->ld_sum < M || ep->ld_sum > (int64_t)1 << 40) return SPMM_E_ARG;
+        if (ot == SPMM_OUT_S32 || (quant && gelu)) return SPMM_E_UNSUPPORTED;
+    }
     spmm::KernelArgs a;
     std::memset(&a, 0, sizeof(a));
     if (quant && gelu) {
@@ -225,9 +229,16 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
     a.x_vec_ok = aligned(X_dev, 16) && (ldx % 16 == 0) && (h->bsr.K * ldx < ((int64_t)1 << 31));
     const int64_t esz = quant ? 1 : 4;
     a.out_vec_ok = aligned(out_dev, 16) && ((ldo * esz) % 16 == 0) && (h->bsr.N * ldo * esz < ((int64_t)1 << 31));
+    if (ep->sum) {
+        a.sum = ep->sum;
+        a.ld_sum = ep->ld_sum;
+        a.out_vec_ok = a.out_vec_ok && aligned(ep->sum, 16) && (ep->ld_sum % 4 == 0) &&
+                       (h->bsr.N * ep->ld_sum * 4 < ((int64_t)1 << 31));
+    }
 
     const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r);
-    const int rc = spmm::launch_spmm(p, a, ot, gelu ? SPMM_POST_GELU : SPMM_POST_NONE, hip_stream);
+    const int rc = spmm::launch_spmm(p, a, ot, (gelu ? SPMM_POST_GELU : SPMM_POST_NONE) | (ep->sum ? spmm::POST_SUM_BIT : 0),
+                                     hip_stream);
     return rc == 0 ? SPMM_OK : SPMM_E_DEVICE;
 }
 

@@ -71,7 +71,8 @@ struct KernelArgs {
     const float* w_scale;
     const float* bias;
     const int8_t* lut;
-    int64_t ldx, ldo;
+    const float* sum;    // Sum post-operator: [N][ld_sum] or nullptr
+    int64_t ldx, ldo, ld_sum;
     int N, K, M;
     int kc, nseg, ntiles;
     int n_tok_tiles, n_row_groups;
@@ -81,6 +82,7 @@ struct KernelArgs {
     float x_scale, inv_out, inv_mid, out_zp_f;
     int x_vec_ok;        // X base 16-byte aligned, ldx % 16 == 0 and K * ldx < 2^31
     int out_vec_ok;      // out base 16-byte aligned, row pitch a multiple of 16 bytes, whole output < 2^31 bytes
+                         // (and, with Sum, the same for the second operand)
 };
 
 struct Plan {
@@ -98,6 +100,8 @@ struct Plan {
 bool plan_supported(int token_tile, int variant);
 Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant);
 // Launches the SpMM kernel; returns a hipError_t value as int (0 = success).
-int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_postop_t postop, void* stream);
+// postop: SPMM_POST_* value, plus POST_SUM_BIT when a.sum is to be added
+constexpr int POST_SUM_BIT = 2;
+int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop, void* stream);
 
 }  // namespace spmm

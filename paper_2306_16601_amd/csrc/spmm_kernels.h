@@ -61,11 +61,14 @@ struct GlobalLut {
     __device__ __forceinline__ uint32_t operator()(uint32_t key) const { return (uint8_t)p[key]; }
 };
 
+// POST template parameters below are the SPMM_POST_* value, plus POST_SUM_BIT when the Sum
+// post-operator (a second binary32 tensor added after BiasAdd / GeLU, before Quantize) is on.
+
 // quantised code of one pre-activation y (Quantize post-operator / table look-up)
 template <int OUT, int POST, typename Lut>
 __device__ __forceinline__ uint32_t quantise(const KernelArgs& a, const float y, const Lut& lut)
 {
-    if constexpr (POST == SPMM_POST_GELU) {
+    if constexpr ((POST & SPMM_POST_GELU) != 0) {
         // key = sat_s8(rint(y / mid_scale)) + 128; v_cvt_pk_u8_f32 converts with saturation to [0, 255]
         const float t = rintf(y * a.inv_mid) + 128.0f;
         return lut(__builtin_amdgcn_cvt_pk_u8_f32(t, 0u, 0u));
@@ -95,11 +98,17 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
         float y[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) y[r] = __fmaf_rn((float)acc[r], s, b);
-        if constexpr (OUT == SPMM_OUT_F32) {
-            if constexpr (POST == SPMM_POST_GELU) {
+        if constexpr (OUT == SPMM_OUT_F32 && (POST & SPMM_POST_GELU) != 0) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) y[r] = gelu_f32(y[r]);
-            }
+            for (int r = 0; r < 4; ++r) y[r] = gelu_f32(y[r]);
+        }
+        if constexpr ((POST & POST_SUM_BIT) != 0) {
+            const float* sp = a.sum + (int64_t)n * a.ld_sum + m0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (r < valid) y[r] = y[r] + sp[r];
+        }
+        if constexpr (OUT == SPMM_OUT_F32) {
             float* o = (float*)a.out + (int64_t)n * a.ldo + m0;
             if (a.out_vec_ok && valid >= 4) {
                 v4f v = {y[0], y[1], y[2], y[3]};
@@ -222,6 +231,8 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
     } else if constexpr (OUT == SPMM_OUT_F32) {
         const uint32_t off = (uint32_t)(tile * TILE_ROWS + c) * (uint32_t)a.ldo + (uint32_t)(tok0 + 4 * g);
         float* o = (float*)a.out + off;
+        // (Sum: the second operand is read in the accumulator layout, 16 bytes per lane)
+        const float* sp = a.sum + ((uint32_t)(tile * TILE_ROWS + c) * (uint32_t)a.ld_sum + (uint32_t)(tok0 + 4 * g));
         if (tile * TILE_ROWS + c < a.N) {
 #pragma unroll
             for (int i = 0; i < G::PIECES; ++i) {
@@ -229,8 +240,9 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     y[r] = __fmaf_rn((float)acc[i][r], scale, bias);
-                    if constexpr (POST == SPMM_POST_GELU) y[r] = gelu_f32(y[r]);
+                    if constexpr ((POST & SPMM_POST_GELU) != 0) y[r] = gelu_f32(y[r]);
                 }
+                if constexpr ((POST & POST_SUM_BIT) != 0) y = y + *(const v4f*)(sp + 16 * i);
                 *(v4f*)(o + 16 * i) = y;
             }
         }
@@ -245,16 +257,24 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
         const int orow = tile * TILE_ROWS + rr;
         const uint32_t off = (uint32_t)orow * (uint32_t)a.ldo + (uint32_t)(tok0 + 16 * rj);
         uint8_t* o = (uint8_t*)a.out + off;
+        // (Sum: read in the accumulator layout, row 16 * tile + c; rows past N are never stored)
+        const bool sum_row_ok = tile * TILE_ROWS + c < a.N;
+        const float* sp = a.sum + ((uint32_t)(tile * TILE_ROWS + c) * (uint32_t)a.ld_sum + (uint32_t)(tok0 + 4 * g));
 #pragma unroll
         for (int h = 0; h < G::HALVES; ++h) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int i = 4 * h + j;
                 if (i >= G::PIECES) continue;   // (a 96-token tile ends after piece 5)
+                v4f y;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) y[r] = __fmaf_rn((float)acc[i][r], scale, bias);
+                if constexpr ((POST & POST_SUM_BIT) != 0) {
+                    if (sum_row_ok) y = y + *(const v4f*)(sp + 16 * i);
+                }
                 uint32_t word = 0;
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    word |= quantise<OUT, POST>(a, __fmaf_rn((float)acc[i][r], scale, bias), lut) << (8 * r);
+                for (int r = 0; r < 4; ++r) word |= quantise<OUT, POST>(a, y[r], lut) << (8 * r);
                 *(uint32_t*)(lds + wbase + (uint32_t)(j ^ wsw) * G::STRIDE) = word;
             }
             const v4i v = *(const v4i*)(lds + raddr);   // same wave: LDS operations complete in order
@@ -311,7 +331,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
             if (a.bias) bias = a.bias[n];
         }
     }
-    if constexpr (POST == SPMM_POST_GELU && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8)) {
+    if constexpr ((POST & SPMM_POST_GELU) != 0 && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8)) {
         if (tid < 256) lds[G::lut_addr(tid)] = (uint8_t)a.lut[tid];
     }
 

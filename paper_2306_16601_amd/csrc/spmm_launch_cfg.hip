@@ -8,28 +8,34 @@
 
 namespace spmm {
 
+// postop: SPMM_POST_NONE / SPMM_POST_GELU, plus POST_SUM_BIT (combinations the host has
+// checked: no Sum with S32 output or with the table chain)
 template <class L>
-static void dispatch_epilogue(spmm_out_t out_type, spmm_postop_t postop, dim3 grid, dim3 block, hipStream_t st,
+static void dispatch_epilogue(spmm_out_t out_type, int postop, dim3 grid, dim3 block, hipStream_t st,
                               const KernelArgs& a)
 {
-    const bool gelu = (postop == SPMM_POST_GELU);
+    const bool gelu = (postop & SPMM_POST_GELU) != 0, sum = (postop & POST_SUM_BIT) != 0;
+    constexpr int NONE = SPMM_POST_NONE, GELU = SPMM_POST_GELU, SUM = POST_SUM_BIT;
     switch (out_type) {
-    case SPMM_OUT_S32: L::template go<SPMM_OUT_S32, SPMM_POST_NONE>(grid, block, st, a); break;
+    case SPMM_OUT_S32: L::template go<SPMM_OUT_S32, NONE>(grid, block, st, a); break;
     case SPMM_OUT_F32:
-        if (gelu) L::template go<SPMM_OUT_F32, SPMM_POST_GELU>(grid, block, st, a);
-        else L::template go<SPMM_OUT_F32, SPMM_POST_NONE>(grid, block, st, a);
+        if (gelu && sum) L::template go<SPMM_OUT_F32, GELU | SUM>(grid, block, st, a);
+        else if (gelu) L::template go<SPMM_OUT_F32, GELU>(grid, block, st, a);
+        else if (sum) L::template go<SPMM_OUT_F32, NONE | SUM>(grid, block, st, a);
+        else L::template go<SPMM_OUT_F32, NONE>(grid, block, st, a);
         break;
     case SPMM_OUT_S8:
-        if (gelu) L::template go<SPMM_OUT_S8, SPMM_POST_GELU>(grid, block, st, a);
-        else L::template go<SPMM_OUT_S8, SPMM_POST_NONE>(grid, block, st, a);
+        if (gelu) L::template go<SPMM_OUT_S8, GELU>(grid, block, st, a);
+        else if (sum) L::template go<SPMM_OUT_S8, NONE | SUM>(grid, block, st, a);
+        else L::template go<SPMM_OUT_S8, NONE>(grid, block, st, a);
         break;
     case SPMM_OUT_U8:
-        if (gelu) L::template go<SPMM_OUT_U8, SPMM_POST_GELU>(grid, block, st, a);
-        else L::template go<SPMM_OUT_U8, SPMM_POST_NONE>(grid, block, st, a);
+        if (gelu) L::template go<SPMM_OUT_U8, GELU>(grid, block, st, a);
+        else if (sum) L::template go<SPMM_OUT_U8, NONE | SUM>(grid, block, st, a);
+        else L::template go<SPMM_OUT_U8, NONE>(grid, block, st, a);
         break;
     }
 }
-
 
 #define SPMM_CAT_(a, b) a##b
 #define SPMM_CAT(a, b) SPMM_CAT_(a, b)
@@ -44,7 +50,7 @@ struct SimpleLaunch {
     }
 };
 
-void SPMM_CAT(launch_cfg_simple_, SPMM_CFG_SIMPLE)(spmm_out_t out_type, spmm_postop_t postop, unsigned grid,
+void SPMM_CAT(launch_cfg_simple_, SPMM_CFG_SIMPLE)(spmm_out_t out_type, int postop, unsigned grid,
                                                    unsigned block, void* stream, const KernelArgs& a)
 {
     dispatch_epilogue<SimpleLaunch<SPMM_CFG_SIMPLE>>(out_type, postop, dim3(grid), dim3(block), (hipStream_t)stream, a);
@@ -60,7 +66,7 @@ struct PipeLaunch {
 };
 
 void SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(launch_cfg_, SPMM_CFG_TM), _), SPMM_CFG_NW), _), SPMM_CFG_MAXS)(
-    spmm_out_t out_type, spmm_postop_t postop, unsigned grid, unsigned block, void* stream, const KernelArgs& a)
+    spmm_out_t out_type, int postop, unsigned grid, unsigned block, void* stream, const KernelArgs& a)
 {
     dispatch_epilogue<PipeLaunch<SPMM_CFG_TM, SPMM_CFG_NW, SPMM_CFG_MAXS>>(out_type, postop, dim3(grid), dim3(block),
                                                                             (hipStream_t)stream, a);

@@ -7,7 +7,7 @@
 namespace spmm {
 
 #define SPMM_DECLARE_CFG(name) \
-    void name(spmm_out_t, spmm_postop_t, unsigned grid, unsigned block, void* stream, const KernelArgs&)
+    void name(spmm_out_t, int postop, unsigned grid, unsigned block, void* stream, const KernelArgs&)
 SPMM_DECLARE_CFG(launch_cfg_128_16_4);
 SPMM_DECLARE_CFG(launch_cfg_128_16_5);
 SPMM_DECLARE_CFG(launch_cfg_128_16_6);
@@ -98,7 +98,7 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
     return p;
 }
 
-int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, spmm_postop_t postop, void* stream)
+int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop, void* stream)
 {
     a.n_tok_tiles = plan.n_tok_tiles;
     a.n_row_groups = plan.n_row_groups;

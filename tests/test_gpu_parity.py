@@ -189,6 +189,71 @@ def test_stacked_qkv_is_three_projections():
     assert np.array_equal(out, np.concatenate(sep))
 
 
+def _run_sum(d, case, R, ld_sum, tuning=None, r_offset=0):
+    h = sp.spmm_pack(d["W"], case.orientation)
+    try:
+        if tuning:
+            sp.spmm_set_tuning(h, *tuning)
+        N, M = case.N, case.M
+        out = torch.full((N, M), POISON[case.out_type], dtype=TORCH_DT[case.out_type], device="cuda")
+        rbuf = torch.full((N * ld_sum + r_offset + 8,), 7.25, dtype=torch.float32, device="cuda")
+        rv = rbuf[r_offset:r_offset + N * ld_sum].view(N, ld_sum)
+        rv[:, :M] = dev(R)
+        w_scale, bias, X = dev(d["w_scale"]), dev(d["bias"]), dev(d["X"])
+        ep = sp.make_epilogue(w_scale, d["x_scale"], d["x_zero_point"], bias, case.postop, case.out_type,
+                              d["out_scale"], d["out_zero_point"], d["mid_scale"], None, rv, ld_sum)
+        sp.spmm_run(h, X, M, M, ep, out, M, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+    finally:
+        sp.spmm_destroy(h)
+
+
+@pytest.mark.parametrize("out_type,postop", [("f32", "none"), ("f32", "gelu"), ("s8", "none"), ("u8", "none")])
+@pytest.mark.parametrize("N,K,M", [(272, 600, 384), (100, 130, 333), (512, 1024, 1000)])
+def test_sum_postop(N, K, M, out_type, postop):
+    # Sum (Figure 3): a second fp32 tensor added after BiasAdd / GeLU and before Quantize
+    case = wl.Case("sum", N, K, M, 0.8, wl.N4K1, out_type, postop, keys=(94, N, K, M))
+    d = wl.make(case)
+    R = (wl.rng_for(95, N, M).standard_normal((N, M)) * wl.preact_sigma(K, case.sparsity)).astype(np.float32)
+    ref = oracle.spmm(d["W"], d["X"], d["w_scale"], d["x_scale"], d["bias"], postop, out_type, d["out_scale"],
+                      d["out_zero_point"], d["mid_scale"], d["x_zero_point"], sum=R)
+    plain = oracle_spmm(d["W"], d["X"], d, case)
+    assert np.mean(ref != plain) > 0.5                     # the residual matters in this test
+    for ld_sum, off, tuning in ((M, 0, None), (M + 4, 0, (96, 16)), (M + 3, 1, None), (M + 8, 4, (128, 8)),
+                                (M, 0, (64, 102))):
+        got = _run_sum(d, case, R, ld_sum, tuning, off)
+        if out_type == "f32" and postop == "gelu":
+            # the two sides' erfc differ by <= 1e-5 relative in GELU(y); the add then rounds once
+            g = np.abs(ref.astype(np.float64) - R.astype(np.float64))
+            tol = 1e-5 * g + 1e-7 + 2.0 ** -23 * np.abs(ref.astype(np.float64))
+            assert (np.abs(got.astype(np.float64) - ref.astype(np.float64)) <= tol).all(), (ld_sum, off, tuning)
+        else:
+            assert_parity(got, ref, case)
+
+
+def test_sum_argument_errors():
+    case = wl.Case("sumerr", 32, 64, 48, 0.5, wl.N4K1, "s8", "gelu", keys=(96,))
+    d = wl.make(case)
+    h = sp.spmm_pack(d["W"])
+    try:
+        X = dev(d["X"])
+        R = torch.zeros((32, 48), dtype=torch.float32, device="cuda")
+        ws, lut = dev(d["w_scale"]), dev(sp.spmm_make_gelu_lut(d["mid_scale"], d["out_scale"], 0, "s8"))
+        out8 = torch.zeros((32, 48), dtype=torch.int8, device="cuda")
+        out32 = torch.zeros((32, 48), dtype=torch.int32, device="cuda")
+        ep = sp.make_epilogue(ws, d["x_scale"], 0, None, "gelu", "s8", d["out_scale"], 0, d["mid_scale"], lut, R, 48)
+        assert sp.spmm_run_status(h, X, 48, 48, ep, out8, 48) == sp.SPMM_E_UNSUPPORTED    # table chain + Sum
+        ep = sp.make_epilogue(ws, d["x_scale"], 0, None, "none", "s32", sum=R, ld_sum=48)
+        assert sp.spmm_run_status(h, X, 48, 48, ep, out32, 48) == sp.SPMM_E_UNSUPPORTED   # raw accumulators + Sum
+        ep = sp.make_epilogue(ws, d["x_scale"], 0, None, "none", "s8", d["out_scale"], 0, sum=R, ld_sum=47)
+        assert sp.spmm_run_status(h, X, 48, 48, ep, out8, 48) == sp.SPMM_E_ARG            # ld_sum < M
+        torch.cuda.synchronize()
+        assert int(out8.abs().sum()) == 0 and int(out32.abs().sum()) == 0                 # outputs untouched
+    finally:
+        sp.spmm_destroy(h)
+
+
 # ---------------------------------------------------------------------------- config 5 (sample of the grid)
 def _grid_sample():
     allc = wl.grid_cases(out_type="s32")
