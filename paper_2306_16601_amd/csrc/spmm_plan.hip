@@ -48,13 +48,17 @@ static void fill_pipelined(Plan& p, int64_t M, int ntiles, int num_cus, int tm, 
     p.workgroups = (int64_t)p.n_row_groups * S;
 }
 
-// Relative duration of a plan: the longest stream's tokens (plus a start-up term, in tokens),
-// times the rounds needed when there are more workgroups than CUs.
+// Relative duration of a plan: the longest stream's tokens times what a token costs a workgroup
+// (plus a start-up term, in tokens), times the rounds needed when there are more workgroups
+// than CUs.  An 8-wave workgroup stages the same activations for half as many rows: measured,
+// its token tile takes about two thirds of a 16-wave one (4096x1024, 90 %: 33.0 against 25.5 us
+// for twice the tiles).
 static double plan_cost(const Plan& p, int num_cus)
 {
     const int per_stream = (p.n_tok_tiles + p.n_streams - 1) / p.n_streams;
     const int64_t rounds = (p.workgroups + num_cus - 1) / num_cus;
-    return (double)rounds * ((double)per_stream * p.token_tile + 48.0);
+    const double per_token = (p.waves == 16) ? 1.0 : 0.66;
+    return (double)rounds * ((double)per_stream * p.token_tile * per_token + 48.0);
 }
 
 Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant)
@@ -80,8 +84,8 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
         fill_pipelined(p, M, ntiles, num_cus, 128, 8);
         return p;
     }
-    if (force_tm) {
-        fill_pipelined(p, M, ntiles, num_cus, force_tm, 16);
+    if (force_tm == 96 || variant == 16) {
+        fill_pipelined(p, M, ntiles, num_cus, force_tm ? force_tm : 128, 16);
         return p;
     }
     // Token tile 128 or 96.  Measured on 6144 tokens: 96-token tiles cost more per token when the
@@ -89,11 +93,19 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
     // per tile weighs more), so they are used only from 5 steps per segment on, and there
     // whenever they do not lengthen the longest stream.
     fill_pipelined(p, M, ntiles, num_cus, 128, 16);
-    if (max_steps >= 5) {
+    if (max_steps >= 5 && force_tm == 0) {
         Plan c{};
         c.max_steps = max_steps;
         fill_pipelined(c, M, ntiles, num_cus, 96, 16);
         if (plan_cost(c, num_cus) <= plan_cost(p, num_cus)) p = c;
+    }
+    {
+        // few row groups and few token tiles (BERT-Base shapes, short batches): 8-wave workgroups
+        // are twice as many and fill more CUs
+        Plan c{};
+        c.max_steps = max_steps;
+        fill_pipelined(c, M, ntiles, num_cus, 128, 8);
+        if (plan_cost(c, num_cus) < plan_cost(p, num_cus)) p = c;
     }
     return p;
 }
