@@ -254,6 +254,33 @@ def test_sum_argument_errors():
         sp.spmm_destroy(h)
 
 
+def test_gelu_f32_dense_sweep_of_preactivations():
+    # One non-zero weight (+1) per row: acc = x in [0, 255], y = x * s[n] + b[n].  Rows are given
+    # scales and biases that make y sweep [-13, 13] in ~260 k distinct steps, dense around 0 and
+    # through the negative tail where GELU is tiny; every value must meet the fp32 bar.
+    N, K, M = 1024, 256, 256
+    W = np.zeros((N, K), np.int8)
+    W[np.arange(N), np.arange(N) % K] = 1
+    X = np.tile(np.arange(256, dtype=np.uint8)[None, :], (K, 1))     # X[k][m] = m: acc[n][m] = m
+    rows = np.arange(N)
+    w_scale = np.where(rows < 512, 26.0 / 255.0, 2.0 / 255.0).astype(np.float32)       # wide / fine sweeps
+    bias = np.where(rows < 512, -13.0 + (rows % 512) * (26.0 / 255.0 / 512.0),
+                    -6.0 + ((rows - 512) // 64) * 1.5 + (rows % 64) * (2.0 / 255.0 / 64.0)).astype(np.float32)
+    d = dict(W=W, X=X, w_scale=w_scale, x_scale=1.0, bias=bias, out_scale=1.0, out_zero_point=0, mid_scale=1.0,
+             x_zero_point=0)
+    case = wl.Case("gelusweep", N, K, M, 0.0, wl.N4K1, "f32", "gelu", keys=(98,))
+    got, ok = gpu_spmm(W, X, d, case)
+    assert ok
+    ref = oracle_spmm(W, X, d, case)
+    y = oracle.spmm(W, X, w_scale, 1.0, bias, "none", "f32")
+    assert y.min() < -12.9 and y.max() > 12.9 and len(np.unique(y)) > 200_000
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    tol = 1e-5 * np.abs(ref.astype(np.float64)) + 1e-7
+    worst = float((err / tol).max())
+    assert worst <= 1.0, "worst error / tolerance = %g at y = %g" % (worst, float(y.flat[int((err / tol).argmax())]))
+    print("gelu sweep: worst error / tolerance = %.4f" % worst)
+
+
 # ---------------------------------------------------------------------------- config 5 (sample of the grid)
 def _grid_sample():
     allc = wl.grid_cases(out_type="s32")
