@@ -329,6 +329,36 @@ def test_every_epilogue_with_unaligned_leading_dims(out_type, postop):
     check_case(case, ldx=112, ldo=96, x_offset=3, out_offset=1)   # misaligned bases
 
 
+def test_largest_reduction_length_and_extreme_sums():
+    # K = 65536 is the largest reduction the 16-bit segment-local indices of the layout are used
+    # with (128 segments); one dense row of +127 and one of -128 against X = 255 reach within 1.2 %
+    # of the int32 range, in the signed-activation form the kernel multiplies in as well.
+    N, K, M = 20, 65536, 40
+    case = wl.Case("maxk", N, K, M, 0.9, wl.N4K1, "s32", "none", keys=(67,))
+    d = wl.make(case)
+    W = d["W"].copy()
+    W[0:4, :] = 127
+    W[4:8, :] = -128
+    X = d["X"].copy()
+    X[:, 0] = 255
+    X[:, 1] = 0
+    d = dict(d, W=W, X=X)
+    got, ok = gpu_spmm(W, X, d, case)
+    ref = oracle_spmm(W, X, d, case)
+    assert ok and np.array_equal(got, ref)
+    assert int(ref[0, 0]) == 65536 * 127 * 255 and int(ref[4, 0]) == -65536 * 128 * 255
+    case8 = case.with_(out_type="s8", postop="gelu")
+    d8 = dict(wl.make(case8), W=W, X=X)
+    got, ok = gpu_spmm(W, X, d8, case8)
+    assert ok and np.array_equal(got, oracle_spmm(W, X, d8, case8))
+    h = None
+    try:
+        with pytest.raises(sp.SpmmError):
+            h = sp.spmm_pack(np.zeros((4, 65537), np.int8))
+    finally:
+        sp.spmm_destroy(h)
+
+
 def test_without_bias_and_with_activation_zero_point():
     case = wl.Case("nobias", 64, 256, 128, 0.8, wl.N4K1, "f32", "none", with_bias=False, keys=(62,))
     check_case(case)
