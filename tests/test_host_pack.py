@@ -210,3 +210,26 @@ def test_step_order_avoids_lds_bank_conflicts(sparsity):
         assert _half_read_conflicts(idx, seg_ptr, n_tiles, n_seg) < 1.0
     finally:
         sp.spmm_destroy(h)
+
+
+def test_plan_picks_token_tile_and_waves_per_shape():
+    """The offline choice of the kernel configuration (host-only handles assume 256 CUs):
+    (token tile, rows per workgroup, workgroups) for the shapes the choices were measured on."""
+    def plan(N, K, M, sparsity, tuning=None):
+        W = wl.sparse_weight(N, K, sparsity, keys=(81, N, K))
+        h = sp.spmm_pack_host(W)
+        try:
+            if tuning:
+                sp.spmm_set_tuning(h, *tuning)
+            return tuple(sp.spmm_plan(h, M, "s8"))
+        finally:
+            sp.spmm_destroy(h)
+
+    assert plan(4096, 1024, 6144, 0.9) == (128, 256, 256)       # 16 row groups x 16 streams of 3 tiles
+    assert plan(1024, 1024, 6144, 0.9) == (128, 256, 192)       # short segments: 128-token tiles
+    assert plan(1024, 1024, 6144, 0.8) == (96, 256, 256)        # 5-6 steps per segment: 64 tiles of 96 fill the CUs
+    assert plan(768, 768, 4096, 0.9) == (128, 128, 192)         # few row groups: 8-wave workgroups
+    assert plan(1024, 1024, 6144, 0.5)[1] == 128                # more than 6 steps per segment: 8 waves
+    assert plan(1024, 1024, 6144, 0.9, (128, 8)) == (128, 128, 256)
+    assert plan(1024, 1024, 6144, 0.9, (96, 16)) == (96, 256, 256)
+    assert plan(256, 256, 128, 0.9, (64, 102))[0] == 64
