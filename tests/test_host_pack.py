@@ -233,3 +233,5 @@ def test_plan_picks_token_tile_and_waves_per_shape():
     assert plan(1024, 1024, 6144, 0.9, (128, 8)) == (128, 128, 256)
     assert plan(1024, 1024, 6144, 0.9, (96, 16)) == (96, 256, 256)
     assert plan(256, 256, 128, 0.9, (64, 102))[0] == 64
+    assert plan(768, 768, 128, 0.9) == (64, 128, 48)             # short batch: the simple kernel's many small workgroups
+    assert plan(768, 768, 128, 0.9, (128, 8)) == (128, 128, 6)
