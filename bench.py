@@ -69,7 +69,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the SpMM shards trivially over tokens or output "
-              "channels, see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+              "channels with no communication); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         return 2
 
     import numpy as np
