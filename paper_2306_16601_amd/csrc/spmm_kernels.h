@@ -274,9 +274,11 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
                 if constexpr ((POST & POST_SUM_BIT) != 0) {
                     if (sum_row_ok) y = y + *(const v4f*)(sp + 16 * i);
                 }
-                uint32_t word = 0;
+                uint32_t q[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) word |= quantise<OUT, POST>(a, y[r], lut) << (8 * r);
+                for (int r = 0; r < 4; ++r) q[r] = quantise<OUT, POST>(a, y[r], lut);
+                // (two shift-or pairs, then one more: three instructions)
+                const uint32_t word = (q[0] | (q[1] << 8)) | ((q[2] | (q[3] << 8)) << 16);
                 *(uint32_t*)(lds + wbase + (uint32_t)(j ^ wsw) * G::STRIDE) = word;
             }
             const v4i v = *(const v4i*)(lds + raddr);   // same wave: LDS operations complete in order
