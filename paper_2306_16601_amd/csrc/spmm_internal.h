@@ -77,7 +77,8 @@ struct KernelArgs {
     int kc, nseg, ntiles;
     int n_tok_tiles, n_row_groups;
     int n_streams;       // persistent kernel: workgroups per row group, each walking token tiles j*n_streams + stream
-    int xcd_map;         // 1: workgroup ids are decoded so that a token-tile stream stays on one XCD
+    int tiles_per_stream, tiles_extra;   // n_tok_tiles = tiles_per_stream * n_streams + tiles_extra
+    int xcd_map;         // simple kernel only: 1 = workgroup ids decoded so that a token tile stays on one XCD
     int corr_mul;        // 128 - x_zero_point: the activations are multiplied as (x - 128)
     float x_scale, inv_out, inv_mid, out_zp_f;
     int x_vec_ok;        // X base 16-byte aligned, ldx % 16 == 0 and K * ldx < 2^31

@@ -306,38 +306,21 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
 
-    // workgroup -> (row group, token-tile stream).  Workgroups go to the 8 XCDs round-robin;
-    // with xcd_map all row groups of one stream get ids congruent mod 8 and share an L2.
-    int rg, stream;
-    {
-        const int b = blockIdx.x;
-        if (a.xcd_map) {
-            const int local = b >> 3;
-            stream = (b & 7) + 8 * (local / a.n_row_groups);
-            rg = local % a.n_row_groups;
-        } else {
-            rg = b % a.n_row_groups;
-            stream = b / a.n_row_groups;
-        }
-    }
+    // workgroup -> (token-tile stream, row group) = (blockIdx.x, blockIdx.y).  Workgroups go to the
+    // 8 XCDs round-robin in linear order (x fastest); the host makes gridDim.x a multiple of 8
+    // whenever it can, so that all row groups of one stream run on the same XCD and share its L2.
+    const int stream = blockIdx.x, rg = blockIdx.y;
     const int S = a.n_streams;
-    const int n_my = (a.n_tok_tiles - stream + S - 1) / S;   // token tiles of this stream (>= 1)
-    const int total = n_my * a.nseg;                          // phases
+    const int n_my = a.tiles_per_stream + (stream < a.tiles_extra ? 1 : 0);   // token tiles of this stream (>= 1)
+    const int total = n_my * a.nseg;                                          // phases
 
     const int tile = rg * NW + wave;
     const bool have_tile = tile < a.ntiles;
     const int n = tile * TILE_ROWS + c;                       // this lane's output row
-    const int init = have_tile ? a.rowsum[n] * a.corr_mul : 0;
+    // per-lane constants of the post-operators: loaded in the start-up sequence below, behind
+    // the activation and weight loads whose latency they would otherwise precede
+    int init = 0;
     float scale = 0.0f, bias = 0.0f;
-    if constexpr (OUT != SPMM_OUT_S32) {
-        if (have_tile && n < a.N) {
-            scale = a.w_scale[n] * a.x_scale;
-            if (a.bias) bias = a.bias[n];
-        }
-    }
-    if constexpr ((POST & SPMM_POST_GELU) != 0 && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8)) {
-        if (tid < 256) lds[G::lut_addr(tid)] = (uint8_t)a.lut[tid];
-    }
 
     v4i A0[MAXS], A1[MAXS];
     uint32_t I0[MAXS], I1[MAXS];
@@ -346,8 +329,6 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     static_assert(XH * 2 == XLOADS, "even number of prefetch loads");
     v4i xr[XH];
     v4i acc[PIECES];
-#pragma unroll
-    for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
 
     // per-thread staging coordinates: XLOADS rows (ROWS_PER_PASS apart), one 16-byte piece
     const bool stager = (STAGERS == NTHREADS) || wave < STAGERS / 64;
@@ -359,7 +340,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     // together; rows past the end of K are redirected to the last valid row (never multiplied).
     // Two halves (first issued at the start of the previous phase, second half-way through its
     // multiply) keep only XH prefetch registers live.
-    auto x_issue = [&](const int q, const int h) {
+    auto x_issue_to = [&](v4i (&xr)[XH], const int q, const int h) {
         const int j = q / a.nseg, seg = q - j * a.nseg;
         const int tok0 = (stream + j * S) * TM;
         const int k0 = seg * SEGMENT_ROWS;
@@ -382,15 +363,25 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         }
     };
     // ---- ... and from registers into LDS buffer q % 2, as x - 128
-    auto x_commit = [&](const int q, const int h) {
+    auto x_commit_from = [&](const v4i (&xr)[XH], const int q, const int h) {
         if (!stager) return;
         uint8_t* buf = lds + (q & 1) * G::BUF + x_lds0 + h * XH * ROWS_PER_PASS * G::STRIDE;
 #pragma unroll
         for (int u = 0; u < XH; ++u)
             *(v4i*)(buf + u * ROWS_PER_PASS * G::STRIDE) = xr[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
     };
+    auto x_issue = [&](const int q, const int h) { x_issue_to(xr, q, h); };
+    auto x_commit = [&](const int q, const int h) { x_commit_from(xr, q, h); };
     // ---- compressed weights + activation-row indices of (tile, segment of phase q).  Loads are
     // unconditional (slots past the segment's step count re-read step 0 and are never used).
+    auto w_issue_at = [&](const int s0, v4i (&A)[MAXS], uint32_t (&I)[MAXS], const int cnt) {
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) {
+            const int step = (s < cnt) ? s0 + s : 0;
+            A[s] = *(const v4i*)(a.vals + (int64_t)step * STEP_VAL_BYTES + lane * 16);
+            I[s] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
+        }
+    };
     auto w_issue = [&](const int q, v4i (&A)[MAXS], uint32_t (&I)[MAXS], int& cnt) {
         cnt = 0;
         int s0 = 0;
@@ -399,12 +390,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
             s0 = a.seg_ptr[tile * a.nseg + seg];
             cnt = a.seg_ptr[tile * a.nseg + seg + 1] - s0;
         }
-#pragma unroll
-        for (int s = 0; s < MAXS; ++s) {
-            const int step = (s < cnt) ? s0 + s : 0;
-            A[s] = *(const v4i*)(a.vals + (int64_t)step * STEP_VAL_BYTES + lane * 16);
-            I[s] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
-        }
+        w_issue_at(s0, A, I, cnt);
     };
     // ---- multiply phase q: gather + transpose out of LDS, PIECES matrix instructions per step.
     // Half-way (after step slot MAXS/2 - 1, executed or not) the first half of the next phase's
@@ -453,11 +439,40 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     };
     const bool reload = a.nseg > 2;   // otherwise set q % 2 always holds segment q % nseg
 
-    x_issue(0, 0);
-    w_issue(0, A0, I0, n0);
-    x_commit(0, 0);
-    x_issue(0, 1);
-    x_commit(0, 1);
+    {   // ---- start-up: every load of the first phase is issued before anything waits -- both
+        // halves of the activations (the second in registers that are not live yet), the weights,
+        // then the per-lane constants and the table -- and consumed in that order
+        v4i x2[XH];
+        // (the step range of the first weights: a scalar load whose latency the address arithmetic
+        // of the activation loads covers)
+        int w_s0 = 0;
+        if (have_tile) {
+            w_s0 = a.seg_ptr[tile * a.nseg];
+            n0 = a.seg_ptr[tile * a.nseg + 1] - w_s0;
+        }
+        x_issue_to(xr, 0, 0);
+        x_issue_to(x2, 0, 1);
+        w_issue_at(w_s0, A0, I0, n0);
+        if (have_tile) init = a.rowsum[n] * a.corr_mul;
+        if constexpr (OUT != SPMM_OUT_S32) {
+            if (have_tile && n < a.N) {
+                scale = a.w_scale[n] * a.x_scale;
+                if (a.bias) bias = a.bias[n];
+            }
+        }
+        constexpr bool TABLE = (POST & SPMM_POST_GELU) != 0 && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8);
+        int table_byte = 0;
+        if constexpr (TABLE) {
+            if (tid < 256) table_byte = a.lut[tid];
+        }
+        x_commit_from(xr, 0, 0);
+        x_commit_from(x2, 0, 1);
+        if constexpr (TABLE) {
+            if (tid < 256) lds[G::lut_addr(tid)] = (uint8_t)table_byte;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
     wait_global_loads();
     __syncthreads();
     for (int p = 0; p < total; p += 2) {

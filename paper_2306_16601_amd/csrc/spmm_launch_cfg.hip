@@ -50,10 +50,12 @@ struct SimpleLaunch {
     }
 };
 
-void SPMM_CAT(launch_cfg_simple_, SPMM_CFG_SIMPLE)(spmm_out_t out_type, int postop, unsigned grid,
-                                                   unsigned block, void* stream, const KernelArgs& a)
+void SPMM_CAT(launch_cfg_simple_, SPMM_CFG_SIMPLE)(spmm_out_t out_type, int postop, unsigned grid_x,
+                                                   unsigned grid_y, unsigned block, void* stream,
+                                                   const KernelArgs& a)
 {
-    dispatch_epilogue<SimpleLaunch<SPMM_CFG_SIMPLE>>(out_type, postop, dim3(grid), dim3(block), (hipStream_t)stream, a);
+    dispatch_epilogue<SimpleLaunch<SPMM_CFG_SIMPLE>>(out_type, postop, dim3(grid_x, grid_y), dim3(block),
+                                                     (hipStream_t)stream, a);
 }
 #else
 template <int TM, int NW, int MAXS>
@@ -66,10 +68,10 @@ struct PipeLaunch {
 };
 
 void SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(launch_cfg_, SPMM_CFG_TM), _), SPMM_CFG_NW), _), SPMM_CFG_MAXS)(
-    spmm_out_t out_type, int postop, unsigned grid, unsigned block, void* stream, const KernelArgs& a)
+    spmm_out_t out_type, int postop, unsigned grid_x, unsigned grid_y, unsigned block, void* stream, const KernelArgs& a)
 {
-    dispatch_epilogue<PipeLaunch<SPMM_CFG_TM, SPMM_CFG_NW, SPMM_CFG_MAXS>>(out_type, postop, dim3(grid), dim3(block),
-                                                                            (hipStream_t)stream, a);
+    dispatch_epilogue<PipeLaunch<SPMM_CFG_TM, SPMM_CFG_NW, SPMM_CFG_MAXS>>(out_type, postop, dim3(grid_x, grid_y),
+                                                                            dim3(block), (hipStream_t)stream, a);
 }
 #endif
 

@@ -7,7 +7,7 @@
 namespace spmm {
 
 #define SPMM_DECLARE_CFG(name) \
-    void name(spmm_out_t, int postop, unsigned grid, unsigned block, void* stream, const KernelArgs&)
+    void name(spmm_out_t, int postop, unsigned grid_x, unsigned grid_y, unsigned block, void* stream, const KernelArgs&)
 SPMM_DECLARE_CFG(launch_cfg_128_16_4);
 SPMM_DECLARE_CFG(launch_cfg_128_16_5);
 SPMM_DECLARE_CFG(launch_cfg_128_16_6);
@@ -131,25 +131,30 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop
     a.n_row_groups = plan.n_row_groups;
     a.n_streams = plan.n_streams;
     a.xcd_map = plan.xcd_map;
-    const unsigned grid = (unsigned)plan.workgroups, block = (unsigned)plan.waves * 64;
+    const unsigned block = (unsigned)plan.waves * 64;
     if (plan.simple) {
-        if (plan.row_tiles_per_wave == 1) launch_cfg_simple_1(out_type, postop, grid, block, stream, a);
-        else if (plan.row_tiles_per_wave == 2) launch_cfg_simple_2(out_type, postop, grid, block, stream, a);
+        const unsigned grid = (unsigned)plan.workgroups;
+        if (plan.row_tiles_per_wave == 1) launch_cfg_simple_1(out_type, postop, grid, 1, block, stream, a);
+        else if (plan.row_tiles_per_wave == 2) launch_cfg_simple_2(out_type, postop, grid, 1, block, stream, a);
         else return (int)hipErrorInvalidValue;
         return (int)hipGetLastError();
     }
     if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
+    // 2-D grid: x = token-tile stream, y = row group
+    const unsigned gx = (unsigned)plan.n_streams, gy = (unsigned)plan.n_row_groups;
+    a.tiles_per_stream = plan.n_tok_tiles / plan.n_streams;
+    a.tiles_extra = plan.n_tok_tiles % plan.n_streams;
     const int maxs = (plan.waves == 8 && plan.max_steps == 5) ? 6 : plan.max_steps;   // no 8-wave 5-step build
     switch (plan.token_tile * 10000 + plan.waves * 100 + maxs) {
-    case 1281604: launch_cfg_128_16_4(out_type, postop, grid, block, stream, a); break;
-    case 1281605: launch_cfg_128_16_5(out_type, postop, grid, block, stream, a); break;
-    case 1281606: launch_cfg_128_16_6(out_type, postop, grid, block, stream, a); break;
-    case 1280804: launch_cfg_128_8_4(out_type, postop, grid, block, stream, a); break;
-    case 1280806: launch_cfg_128_8_6(out_type, postop, grid, block, stream, a); break;
-    case 1280808: launch_cfg_128_8_8(out_type, postop, grid, block, stream, a); break;
-    case 961604: launch_cfg_96_16_4(out_type, postop, grid, block, stream, a); break;
-    case 961605: launch_cfg_96_16_5(out_type, postop, grid, block, stream, a); break;
-    case 961606: launch_cfg_96_16_6(out_type, postop, grid, block, stream, a); break;
+    case 1281604: launch_cfg_128_16_4(out_type, postop, gx, gy, block, stream, a); break;
+    case 1281605: launch_cfg_128_16_5(out_type, postop, gx, gy, block, stream, a); break;
+    case 1281606: launch_cfg_128_16_6(out_type, postop, gx, gy, block, stream, a); break;
+    case 1280804: launch_cfg_128_8_4(out_type, postop, gx, gy, block, stream, a); break;
+    case 1280806: launch_cfg_128_8_6(out_type, postop, gx, gy, block, stream, a); break;
+    case 1280808: launch_cfg_128_8_8(out_type, postop, gx, gy, block, stream, a); break;
+    case 961604: launch_cfg_96_16_4(out_type, postop, gx, gy, block, stream, a); break;
+    case 961605: launch_cfg_96_16_5(out_type, postop, gx, gy, block, stream, a); break;
+    case 961606: launch_cfg_96_16_6(out_type, postop, gx, gy, block, stream, a); break;
     default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();
