@@ -48,7 +48,7 @@ typedef enum {
     SPMM_BLOCK_N1K4 = 1  /* 1 output row x 4 consecutive k  */
 } spmm_block_t;
 
-typedef enum { SPMM_POST_NONE = 0, SPMM_POST_GELU = 1 } spmm_postop_t;
+typedef enum { SPMM_POST_NONE = 0, SPMM_POST_GELU = 1, SPMM_POST_TABLE = 2 } spmm_postop_t;
 
 typedef enum {
     SPMM_OUT_S32 = 0, /* raw accumulator; scales, bias and post-op are ignored */
@@ -69,6 +69,8 @@ typedef enum {
  *            (GELU + S8/U8), whose value is a function of one key: SPMM_E_UNSUPPORTED.
  *   S8/U8 out without GELU: q = sat(rint(z * (1/out_scale)) + out_zero_point)
  *   S8/U8 out with GELU   : t = sat_s8(rint(y * (1/mid_scale)));  q = lut[t + 128]
+ *   POST_TABLE (S8/U8 out only): the same look-up with the caller's own 256-entry table of any
+ *            element-wise chain (Algorithm 2 in general; other output types: SPMM_E_UNSUPPORTED)
  * rint is round-half-to-even; 1/scale is one binary32 division done on the host.
  */
 typedef struct {
@@ -80,8 +82,9 @@ typedef struct {
     spmm_out_t out_type;
     float out_scale;        /* S8/U8 without GELU: output quantisation scale (> 0)       */
     int32_t out_zero_point; /* S8/U8 without GELU                                        */
-    float mid_scale;        /* GELU + S8/U8: scale of the pre-activation code (> 0)      */
-    const int8_t *lut;      /* GELU + S8/U8: device [256] table from spmm_make_gelu_lut  */
+    float mid_scale;        /* GELU / TABLE + S8/U8: scale of the pre-activation code (> 0) */
+    const int8_t *lut;      /* GELU / TABLE + S8/U8: device [256] table (spmm_make_gelu_lut
+                               builds the GELU one)                                        */
     const float *sum;       /* device [N][ld_sum] binary32 or NULL: operand of Sum       */
     int64_t ld_sum;         /* >= M when sum is given (in elements)                       */
 } spmm_epilogue_t;

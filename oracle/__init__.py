@@ -16,7 +16,7 @@ import numpy as np
 from .build import build as _build
 
 OUT_TYPES = {"s32": 0, "f32": 1, "s8": 2, "u8": 3}
-POSTOPS = {"none": 0, "gelu": 1}
+POSTOPS = {"none": 0, "gelu": 1, "table": 2}
 _OUT_DTYPES = {"s32": np.int32, "f32": np.float32, "s8": np.int8, "u8": np.uint8}
 
 _lib = None

@@ -22,6 +22,8 @@
  *   y         = fmaf((float)acc, s[n], bias ? bias[n] : 0)  one fused binary32 op
  *   GELU, f32 out :  z = (float)(0.5 * y * erfc(-y / sqrt(2)))   evaluated in double
  *   GELU, int8 out:  t = sat_s8(rintf(y * (1.0f / mid_scale)));  q = lut[t + 128]
+ *   TABLE, int8 out: the same look-up with a caller's table of any element-wise chain (Algorithm 2
+ *                    is stated for a post-operator chain in general; GELU is the instance above)
  *   no post-op    :  z = y
  *   Sum (optional):  z = z + R[n][m]       one binary32 add of a second [N][M] tensor
  *                    (Figure 3 names Sum among the fused post-operators without a formula;
@@ -40,7 +42,7 @@
 #endif
 
 enum { ORACLE_OUT_S32 = 0, ORACLE_OUT_F32 = 1, ORACLE_OUT_S8 = 2, ORACLE_OUT_U8 = 3 };
-enum { ORACLE_POST_NONE = 0, ORACLE_POST_GELU = 1 };
+enum { ORACLE_POST_NONE = 0, ORACLE_POST_GELU = 1, ORACLE_POST_TABLE = 2 };
 
 /* Exact (erf-based) GELU in double: x * Phi(x), Phi written with erfc so the
  * negative tail keeps its relative accuracy. */
@@ -105,16 +107,18 @@ int oracle_epilogue_sum(const int32_t *acc, int64_t N, int64_t M,
                         float mid_scale, const int8_t *lut, void *out, int64_t ldo)
 {
     if (out_type < ORACLE_OUT_S32 || out_type > ORACLE_OUT_U8) return -1;
-    if (postop != ORACLE_POST_NONE && postop != ORACLE_POST_GELU) return -1;
+    if (postop != ORACLE_POST_NONE && postop != ORACLE_POST_GELU && postop != ORACLE_POST_TABLE) return -1;
     const int quant = (out_type == ORACLE_OUT_S8 || out_type == ORACLE_OUT_U8);
     if (out_type != ORACLE_OUT_S32 && !w_scale) return -1;
-    if (postop == ORACLE_POST_GELU && quant && !lut) return -1;
-    if (sum && (out_type == ORACLE_OUT_S32 || (postop == ORACLE_POST_GELU && quant))) return -1;
+    if (postop == ORACLE_POST_TABLE && !quant) return -1;
+    const int table = quant && (postop == ORACLE_POST_GELU || postop == ORACLE_POST_TABLE);
+    if (table && !lut) return -1;
+    if (sum && (out_type == ORACLE_OUT_S32 || table)) return -1;
 
     const float lo = (out_type == ORACLE_OUT_U8) ? 0.0f : -128.0f;
     const float hi = (out_type == ORACLE_OUT_U8) ? 255.0f : 127.0f;
     const float inv_out = quant ? 1.0f / out_scale : 0.0f;
-    const float inv_mid = (quant && postop == ORACLE_POST_GELU) ? 1.0f / mid_scale : 0.0f;
+    const float inv_mid = table ? 1.0f / mid_scale : 0.0f;
 
 #pragma omp parallel for schedule(static)
     for (int64_t n = 0; n < N; ++n) {
@@ -137,7 +141,7 @@ int oracle_epilogue_sum(const int32_t *acc, int64_t N, int64_t M,
                 continue;
             }
             int q;
-            if (postop == ORACLE_POST_GELU) {
+            if (table) {
                 const int t = (int)sat_round(rintf(y * inv_mid), -128.0f, 127.0f);
                 q = (out_type == ORACLE_OUT_U8) ? (int)(uint8_t)lut[t + 128] : (int)lut[t + 128];
             } else {

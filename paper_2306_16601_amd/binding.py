@@ -19,11 +19,11 @@ LIB_PATH = os.path.join(HERE, "libspmm4x1.so")
 
 SPMM_OK, SPMM_E_ARG, SPMM_E_UNSUPPORTED, SPMM_E_ALLOC, SPMM_E_DEVICE = range(5)
 SPMM_BLOCK_N4K1, SPMM_BLOCK_N1K4 = 0, 1
-SPMM_POST_NONE, SPMM_POST_GELU = 0, 1
+SPMM_POST_NONE, SPMM_POST_GELU, SPMM_POST_TABLE = 0, 1, 2
 SPMM_OUT_S32, SPMM_OUT_F32, SPMM_OUT_S8, SPMM_OUT_U8 = 0, 1, 2, 3
 
 BLOCKS = {"n4k1": SPMM_BLOCK_N4K1, "n1k4": SPMM_BLOCK_N1K4}
-POSTOPS = {"none": SPMM_POST_NONE, "gelu": SPMM_POST_GELU}
+POSTOPS = {"none": SPMM_POST_NONE, "gelu": SPMM_POST_GELU, "table": SPMM_POST_TABLE}
 OUT_TYPES = {"s32": SPMM_OUT_S32, "f32": SPMM_OUT_F32, "s8": SPMM_OUT_S8, "u8": SPMM_OUT_U8}
 
 EXPORTS = (

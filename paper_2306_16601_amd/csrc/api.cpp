@@ -192,10 +192,12 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
     const spmm_out_t ot = ep->out_type;
     const spmm_postop_t po = ep->postop;
     if (ot != SPMM_OUT_S32 && ot != SPMM_OUT_F32 && ot != SPMM_OUT_S8 && ot != SPMM_OUT_U8) return SPMM_E_ARG;
-    if (po != SPMM_POST_NONE && po != SPMM_POST_GELU) return SPMM_E_ARG;
+    if (po != SPMM_POST_NONE && po != SPMM_POST_GELU && po != SPMM_POST_TABLE) return SPMM_E_ARG;
     if (ep->x_zero_point < 0 || ep->x_zero_point > 255) return SPMM_E_ARG;
     const bool quant = (ot == SPMM_OUT_S8 || ot == SPMM_OUT_U8);
-    const bool gelu = (po == SPMM_POST_GELU);
+    if (po == SPMM_POST_TABLE && !quant) return SPMM_E_UNSUPPORTED;
+    // with a 1-byte output GELU is itself a table look-up: TABLE runs the same kernels
+    const bool gelu = (po == SPMM_POST_GELU || po == SPMM_POST_TABLE);
     if (ot != SPMM_OUT_S32) {
         if (!ep->w_scale) return SPMM_E_ARG;
         if (!(ep->x_scale == ep->x_scale)) return SPMM_E_ARG;   // NaN
@@ -267,7 +269,8 @@ spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t 
 {
     if (!h || M <= 0 || !buf || buflen <= 0) return SPMM_E_ARG;
     if (out_type < SPMM_OUT_S32 || out_type > SPMM_OUT_U8) return SPMM_E_ARG;
-    if (postop != SPMM_POST_NONE && postop != SPMM_POST_GELU) return SPMM_E_ARG;
+    if (postop != SPMM_POST_NONE && postop != SPMM_POST_GELU && postop != SPMM_POST_TABLE) return SPMM_E_ARG;
+    if (postop == SPMM_POST_TABLE) postop = SPMM_POST_GELU;   // same kernels
     const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r);
     const int post = (out_type == SPMM_OUT_S32) ? 0 : (int)postop;   // S32 output ignores the post-operator
     if (p.simple)

@@ -137,7 +137,7 @@ def _run_with_table(d, case, table):
     try:
         out = torch.empty((case.N, case.M), dtype=TORCH_DT[case.out_type], device="cuda")
         w_scale, bias, lut, X = dev(d["w_scale"]), dev(d["bias"]), dev(table), dev(d["X"])   # alive until the sync
-        ep = sp.make_epilogue(w_scale, d["x_scale"], d["x_zero_point"], bias, "gelu",
+        ep = sp.make_epilogue(w_scale, d["x_scale"], d["x_zero_point"], bias, "table",
                               case.out_type, d["out_scale"], d["out_zero_point"], d["mid_scale"], lut)
         sp.spmm_run(h, X, case.M, case.M, ep, out, case.M, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
@@ -160,7 +160,7 @@ def test_table_of_any_elementwise_chain(out_type):
     for table in (tanh_q, perm):
         table = table.astype(np.uint8 if out_type == "u8" else np.int8)
         got = _run_with_table(d, case, table.view(np.int8))
-        ref = oracle.spmm(d["W"], d["X"], d["w_scale"], d["x_scale"], d["bias"], "gelu", out_type, d["out_scale"],
+        ref = oracle.spmm(d["W"], d["X"], d["w_scale"], d["x_scale"], d["bias"], "table", out_type, d["out_scale"],
                           d["out_zero_point"], d["mid_scale"], d["x_zero_point"], lut=table)
         assert np.array_equal(got, ref)
         assert len(np.unique(got)) > 8      # the table is really exercised

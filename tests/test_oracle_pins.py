@@ -368,6 +368,17 @@ def test_gelu_int8_path_is_quantise_then_table():
     a = oracle.acc_s32(W, X)
     full = oracle.spmm(W, X, w_scale, 0.02, bias, "gelu", "s8", outs, 0, mid)
     assert np.array_equal(full, oracle.epilogue(a, w_scale, 0.02, bias, "gelu", "s8", outs, 0, mid, lut))
+    # a caller's table of some other chain goes through the same look-up ("table" post-operator)
+    other = rng.integers(-128, 128, size=256).astype(np.int8)
+    got = oracle.epilogue(acc, w_scale, 0.02, bias, "table", "s8", outs, 0, mid, other)
+    for n in range(N):
+        for m in range(M):
+            t = min(127, max(-128, py_round_half_even(float(np.float32(y[n, m]) * inv))))
+            assert int(got[n, m]) == int(other[t + 128])
+    with pytest.raises(ValueError):      # a table yields low-precision codes only
+        oracle.epilogue(acc, w_scale, 0.02, bias, "table", "f32", outs, 0, mid, other)
+    with pytest.raises(ValueError):
+        oracle.epilogue(acc, w_scale, 0.02, bias, "table", "s8", outs, 0, mid, None)
 
 
 # ----------------------------------------------------------------------------
