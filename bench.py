@@ -56,6 +56,9 @@ def main() -> int:
     ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "large_sum"],
                     help="large_sum: the two BERT-Large Linears that feed a residual add (attention output and "
                          "second feed-forward), with the Sum post-operator and fp32 output")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="workload base only: token count M (default 4096 = 32 sequences of 128)")
+    ap.add_argument("--sparsities", default="", help="workload base only: comma list, e.g. 0.7,0.8,0.9")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--tuning", default="", help="token_tile,variant override passed to spmm_set_tuning")
@@ -89,8 +92,13 @@ def main() -> int:
         cases = wl.large_cases()
         wname = "bert_large_layers_m6144_s90_s80_gelu_s8"
     elif args.workload == "base":
-        cases = [c for c in wl.base_cases(batches=(32,), sparsities=(0.9, 0.8))]
+        sps = tuple(float(v) for v in args.sparsities.split(",")) if args.sparsities else (0.9, 0.8)
+        cases = [c for c in wl.base_cases(batches=(32,), sparsities=sps)]
         wname = "bert_base_layers_m4096_s90_s80_f32"
+        if args.tokens or args.sparsities:
+            M = args.tokens or 4096
+            cases = [c.with_(M=M, name=c.name.replace("_m4096_", "_m%d_" % M)) for c in cases]
+            wname = "bert_base_layers_m%d_s%s_f32" % (M, "_".join(str(int(round(v * 100))) for v in sps))
     elif args.workload == "large_sum":
         cases = [c.with_(out_type="f32", postop="none") for c in wl.large_cases() if c.N == 1024]
         wname = "bert_large_residual_linears_m6144_s90_s80_sum_f32"

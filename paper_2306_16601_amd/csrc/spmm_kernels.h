@@ -541,16 +541,44 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
         for (int i = 0; i < PIECES; ++i) acc[r][i] = (v4i){init, init, init, init};
     }
 
-    for (int seg = 0; seg < a.nseg; ++seg) {
-        const int k0 = seg * a.kc;
-        const int rows = min(a.kc, a.K - k0);
-        if (seg > 0) __syncthreads();
-        for (int p = tid; p < rows * PIECES; p += NW * 64) {
-            const int row = p / PIECES, piece = p % PIECES;
-            const v4i v = load_x16(a, k0 + row, tok0 + piece * 16);
-            *(v4i*)(lds + row * STRIDE + piece * 16) = v ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+    // Staging: XL 16-byte pieces per thread and segment.  The pieces of segment seg + 1 are
+    // requested before segment seg is multiplied and written to the (single) LDS buffer after it,
+    // so their latency hides behind the multiply.
+    constexpr int XL = SEGMENT_ROWS * PIECES / (NW * 64);
+    static_assert(XL * NW * 64 == SEGMENT_ROWS * PIECES, "threads must tile a segment");
+    v4i xs[XL];
+    auto x_load = [&](const int seg) __attribute__((always_inline)) {
+        const int k0 = seg * SEGMENT_ROWS;
+        const int last = min(SEGMENT_ROWS, a.K - k0) - 1;      // rows past K repeat the last one (never multiplied)
+        if (a.x_vec_ok && tok0 + TM <= a.M) {
+            const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0;
+#pragma unroll
+            for (int u = 0; u < XL; ++u) {
+                const int p = tid + u * NW * 64;
+                const int row = min(p / PIECES, last), piece = p % PIECES;
+                xs[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(piece * 16)));
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < XL; ++u) {
+                const int p = tid + u * NW * 64;
+                const int row = min(p / PIECES, last), piece = p % PIECES;
+                xs[u] = load_x16(a, k0 + row, tok0 + piece * 16);
+            }
         }
-        __syncthreads();
+    };
+    auto x_store = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < XL; ++u) {
+            const int p = tid + u * NW * 64;
+            *(v4i*)(lds + (p / PIECES) * STRIDE + (p % PIECES) * 16) = xs[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+        }
+    };
+    x_load(0);
+    x_store();
+    __syncthreads();
+    for (int seg = 0; seg < a.nseg; ++seg) {
+        if (seg + 1 < a.nseg) x_load(seg + 1);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int tile = (rg * NW + wave) * R + r;
@@ -570,6 +598,11 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
                     acc[r][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, w, acc[r][i], 0, 0, 0);
                 }
             }
+        }
+        if (seg + 1 < a.nseg) {
+            __syncthreads();   // everyone has finished reading this segment
+            x_store();
+            __syncthreads();
         }
     }
 

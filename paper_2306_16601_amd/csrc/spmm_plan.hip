@@ -88,24 +88,21 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
     // waves, 256 registers and half as many rows per workgroup (token tile 128 only).
     if (max_steps > 6 || variant == 8) {
         fill_pipelined(p, M, ntiles, num_cus, 128, 8);
-        return p;
-    }
-    if (force_tm == 96 || variant == 16) {
+    } else if (force_tm == 96 || variant == 16) {
         fill_pipelined(p, M, ntiles, num_cus, force_tm ? force_tm : 128, 16);
         return p;
-    }
-    // Token tile 128 or 96.  Measured on 6144 tokens: 96-token tiles cost more per token when the
-    // segments are short (the activation rows no longer fill cache lines, and the fixed work
-    // per tile weighs more), so they are used only from 5 steps per segment on, and there
-    // whenever they do not lengthen the longest stream.
-    fill_pipelined(p, M, ntiles, num_cus, 128, 16);
-    if (max_steps >= 5 && force_tm == 0) {
-        Plan c{};
-        c.max_steps = max_steps;
-        fill_pipelined(c, M, ntiles, num_cus, 96, 16);
-        if (plan_cost(c, num_cus) <= plan_cost(p, num_cus)) p = c;
-    }
-    {
+    } else {
+        // Token tile 128 or 96.  Measured on 6144 tokens: 96-token tiles cost more per token when
+        // the segments are short (the activation rows no longer fill cache lines, and the fixed
+        // work per tile weighs more), so they are used only from 5 steps per segment on, and
+        // there whenever they do not lengthen the longest stream.
+        fill_pipelined(p, M, ntiles, num_cus, 128, 16);
+        if (max_steps >= 5 && force_tm == 0) {
+            Plan c{};
+            c.max_steps = max_steps;
+            fill_pipelined(c, M, ntiles, num_cus, 96, 16);
+            if (plan_cost(c, num_cus) <= plan_cost(p, num_cus)) p = c;
+        }
         // few row groups and few token tiles (BERT-Base shapes, short batches): 8-wave workgroups
         // are twice as many and fill more CUs
         Plan c{};
@@ -120,7 +117,7 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
         Plan c{};
         c.max_steps = max_steps;
         fill_simple(c, M, ntiles, 1);
-        if (c.workgroups > p.workgroups) p = c;
+        if ((int64_t)c.n_row_groups * c.n_tok_tiles >= p.workgroups) p = c;   // (its grid is padded to the XCDs)
     }
     return p;
 }
