@@ -354,6 +354,18 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
                 const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
                 xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(x_piece * 16)));
             }
+        } else if (a.x_vec_ok && (a.M & 15) == 0) {
+            // ragged last tile of an aligned matrix whose token count is a multiple of 16: a piece
+            // is either whole or beyond the end, still branch-free
+            const uint8_t* src = a.X + (int64_t)k0 * a.ldx;
+            const int col = tok0 + x_piece * 16;
+            const bool in = col < a.M;
+#pragma unroll
+            for (int u = 0; u < XH; ++u) {
+                const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
+                const v4i v = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(in ? col : 0)));
+                xr[u] = in ? v : (v4i){0, 0, 0, 0};
+            }
         } else {
 #pragma unroll
             for (int u = 0; u < XH; ++u) {
@@ -557,6 +569,17 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
                 const int p = tid + u * NW * 64;
                 const int row = min(p / PIECES, last), piece = p % PIECES;
                 xs[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(piece * 16)));
+            }
+        } else if (a.x_vec_ok && (a.M & 15) == 0) {
+            // ragged last tile, token count a multiple of 16: whole pieces or none, branch-free
+            const uint8_t* src = a.X + (int64_t)k0 * a.ldx;
+#pragma unroll
+            for (int u = 0; u < XL; ++u) {
+                const int p = tid + u * NW * 64;
+                const int row = min(p / PIECES, last), col = tok0 + (p % PIECES) * 16;
+                const bool in = col < a.M;
+                const v4i v = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(in ? col : 0)));
+                xs[u] = in ? v : (v4i){0, 0, 0, 0};
             }
         } else {
 #pragma unroll
