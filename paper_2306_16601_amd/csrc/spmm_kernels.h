@@ -538,16 +538,21 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
 }
 
 // =======================================================================================
-// Simple kernel (token tile 64, one K segment in LDS, no software pipelining, table read
-// from global memory): an independent second implementation of the same layout, selected
-// with spmm_set_tuning(h, 64, 101 or 102).  Different tilings must agree bit for bit because
-// int32 accumulation is order-free.
+// Simple kernel (token tile 64, 32 or 16, one K segment in LDS, no software pipelining, table
+// read from global memory): an independent second implementation of the same layout, selected
+// with spmm_set_tuning(h, 64 / 32 / 16, 101 or 102) and, automatically, for problems too small
+// to fill the chip (there the narrowest token tile that still fits one workgroup per CU: a
+// workgroup's time is bound by its CU's LDS, so narrower tiles on more CUs finish sooner).
+// Different tilings must agree bit for bit because int32 accumulation is order-free.
 // =======================================================================================
 template <int TM, int NW, int R, int OUT, int POST>
 __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const KernelArgs a)
 {
-    constexpr int STRIDE = TM + 16;
+    // row pitch in LDS: 80 / 48 / 48 bytes = 20 / 12 / 12 banks, so that 16 rows whose indices
+    // differ mod 16 (the packer's order) start in 16 different groups of four banks
+    constexpr int STRIDE = (TM == 16) ? 48 : TM + 16;
     constexpr int PIECES = TM / 16;
+    static_assert(TM == 64 || TM == 32 || TM == 16, "token tile of the simple kernel");
     __shared__ __attribute__((aligned(16))) uint8_t lds[SEGMENT_ROWS * STRIDE];
 
     const int b = blockIdx.x;

@@ -1,7 +1,8 @@
 // One kernel configuration of the SpMM kernels: this file is compiled once per configuration
 // (see build.py), so that the instantiations build in parallel.
 //   pipelined kernel : -DSPMM_CFG_TM=<128|96> -DSPMM_CFG_NW=<16|8> -DSPMM_CFG_MAXS=<4|5|6|8>
-//   simple kernel    : -DSPMM_CFG_SIMPLE=<1|2>      (row tiles per wave)
+//   simple kernel    : -DSPMM_CFG_SIMPLE=<1|2>      (row tiles per wave; token tile 64)
+//                      -DSPMM_CFG_SIMPLE=1 -DSPMM_CFG_SIMPLE_TM=<32|16>
 // Each defines one function launch_cfg_<...>() that picks the epilogue instantiation and
 // launches it; spmm_plan.hip calls them.
 #include "spmm_kernels.h"
@@ -41,16 +42,23 @@ static void dispatch_epilogue(spmm_out_t out_type, int postop, dim3 grid, dim3 b
 #define SPMM_CAT(a, b) SPMM_CAT_(a, b)
 
 #ifdef SPMM_CFG_SIMPLE
+#ifdef SPMM_CFG_SIMPLE_TM
+#define SPMM_SIMPLE_NAME SPMM_CAT(SPMM_CAT(launch_cfg_simple, SPMM_CFG_SIMPLE_TM), _)
+#else
+#define SPMM_CFG_SIMPLE_TM 64
+#define SPMM_SIMPLE_NAME launch_cfg_simple_
+#endif
+
 template <int R>
 struct SimpleLaunch {
     template <int OUT, int POST>
     static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
     {
-        hipLaunchKernelGGL((spmm_rowtile_mfma_simple<64, 8, R, OUT, POST>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((spmm_rowtile_mfma_simple<SPMM_CFG_SIMPLE_TM, 8, R, OUT, POST>), grid, block, 0, st, a);
     }
 };
 
-void SPMM_CAT(launch_cfg_simple_, SPMM_CFG_SIMPLE)(spmm_out_t out_type, int postop, unsigned grid_x,
+void SPMM_CAT(SPMM_SIMPLE_NAME, SPMM_CFG_SIMPLE)(spmm_out_t out_type, int postop, unsigned grid_x,
                                                    unsigned grid_y, unsigned block, void* stream,
                                                    const KernelArgs& a)
 {

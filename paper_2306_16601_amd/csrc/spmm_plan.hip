@@ -19,6 +19,8 @@ SPMM_DECLARE_CFG(launch_cfg_96_16_5);
 SPMM_DECLARE_CFG(launch_cfg_96_16_6);
 SPMM_DECLARE_CFG(launch_cfg_simple_1);
 SPMM_DECLARE_CFG(launch_cfg_simple_2);
+SPMM_DECLARE_CFG(launch_cfg_simple32_1);
+SPMM_DECLARE_CFG(launch_cfg_simple16_1);
 #undef SPMM_DECLARE_CFG
 
 bool plan_supported(int token_tile, int variant)
@@ -26,6 +28,7 @@ bool plan_supported(int token_tile, int variant)
     if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16;
     if (token_tile == 96) return variant == 0 || variant == 16;
     if (token_tile == 64) return variant == 101 || variant == 102;
+    if (token_tile == 32 || token_tile == 16) return variant == 101;
     return false;
 }
 
@@ -48,14 +51,14 @@ static void fill_pipelined(Plan& p, int64_t M, int ntiles, int num_cus, int tm, 
     p.workgroups = (int64_t)p.n_row_groups * S;
 }
 
-// Simple kernel: 64-token tiles, 8 waves with r row tiles each, one workgroup per (row group, tile).
-static void fill_simple(Plan& p, int64_t M, int ntiles, int r)
+// Simple kernel: tm-token tiles, 8 waves with r row tiles each, one workgroup per (row group, tile).
+static void fill_simple(Plan& p, int64_t M, int ntiles, int r, int tm)
 {
-    p.token_tile = 64;
+    p.token_tile = tm;
     p.waves = 8;
     p.row_tiles_per_wave = r;
     p.simple = 1;
-    p.n_tok_tiles = (int)((M + 63) / 64);
+    p.n_tok_tiles = (int)((M + tm - 1) / tm);
     p.n_row_groups = (ntiles + p.waves * r - 1) / (p.waves * r);
     p.n_streams = 0;
     p.xcd_map = 1;
@@ -80,8 +83,8 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
     Plan p{};
     const int max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? max_steps_per_segment : 8);
     p.max_steps = max_steps;
-    if (force_tm == 64) {
-        fill_simple(p, M, ntiles, variant - 100);
+    if (force_tm == 64 || force_tm == 32 || force_tm == 16) {
+        fill_simple(p, M, ntiles, variant - 100, force_tm);
         return p;
     }
     // 16 waves have 128 registers each: at most 6 steps per segment; denser weights run with 8
@@ -116,8 +119,17 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
         // the faster one there (768x768, 128..1024 tokens: 5.8-6.0 us against 7.5-7.9 us).
         Plan c{};
         c.max_steps = max_steps;
-        fill_simple(c, M, ntiles, 1);
-        if ((int64_t)c.n_row_groups * c.n_tok_tiles >= p.workgroups) p = c;   // (its grid is padded to the XCDs)
+        fill_simple(c, M, ntiles, 1, 64);
+        if ((int64_t)c.n_row_groups * c.n_tok_tiles >= p.workgroups) {   // (its grid is padded to the XCDs)
+            p = c;
+            // A simple-kernel workgroup is bound by its own CU's LDS (8 waves gathering from one
+            // staged segment), so while CUs are idle, narrower token tiles on more CUs finish
+            // sooner: the narrowest tile that still gives every workgroup a CU of its own.
+            for (int tm = 32; tm >= 16; tm /= 2) {
+                fill_simple(c, M, ntiles, 1, tm);
+                if ((int64_t)c.n_row_groups * c.n_tok_tiles <= num_cus) p = c;
+            }
+        }
     }
     return p;
 }
@@ -131,8 +143,11 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop
     const unsigned block = (unsigned)plan.waves * 64;
     if (plan.simple) {
         const unsigned grid = (unsigned)plan.workgroups;
-        if (plan.row_tiles_per_wave == 1) launch_cfg_simple_1(out_type, postop, grid, 1, block, stream, a);
-        else if (plan.row_tiles_per_wave == 2) launch_cfg_simple_2(out_type, postop, grid, 1, block, stream, a);
+        const int key = plan.token_tile * 10 + plan.row_tiles_per_wave;
+        if (key == 641) launch_cfg_simple_1(out_type, postop, grid, 1, block, stream, a);
+        else if (key == 642) launch_cfg_simple_2(out_type, postop, grid, 1, block, stream, a);
+        else if (key == 321) launch_cfg_simple32_1(out_type, postop, grid, 1, block, stream, a);
+        else if (key == 161) launch_cfg_simple16_1(out_type, postop, grid, 1, block, stream, a);
         else return (int)hipErrorInvalidValue;
         return (int)hipGetLastError();
     }
