@@ -173,7 +173,15 @@ spmm_status_t spmm_plan(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
  *   token_tile  96: the same kernel on 96-token tiles, variant 0 or 16 (16 waves; denser
  *                   weights silently use token tile 128 with 8 waves).
  *   token_tile  64: variant 101 / 102 = the simple, unpipelined kernel with 1 / 2 row tiles
- *                   per wave (an independent second implementation for cross-checks).
+ *                   per wave (an independent second implementation for cross-checks, and the
+ *                   automatic choice for problems too small to fill the chip).
+ *   token_tile 32, 16: variant 101 = the simple kernel on narrower token tiles (what the
+ *                   automatic choice takes for short batches: more, smaller workgroups).
+ *   token_tile  16: variant 103 = the short-batch kernel, which keeps a workgroup's whole
+ *                   [K x 16] slab of activations in LDS (K <= 4096; a longer K silently runs
+ *                   variant 101).  The automatic choice for short batches with 2048 < K <= 4096:
+ *                   Section 4.3 measures the kernels at 32 tokens and the models at sequence
+ *                   lengths of 16 to 384.
  * Unsupported values return SPMM_E_UNSUPPORTED and change nothing.  Not thread-safe against
  * concurrent spmm_run on the same handle. */
 spmm_status_t spmm_set_tuning(spmm_handle_t *h, int32_t token_tile, int32_t variant);

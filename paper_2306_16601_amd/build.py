@@ -44,6 +44,7 @@ def units():
         out.append((f"cfg_simple_{r}.o", cfg, [f"-DSPMM_CFG_SIMPLE={r}"]))
     for tm in SIMPLE_NARROW:
         out.append((f"cfg_simple{tm}_1.o", cfg, ["-DSPMM_CFG_SIMPLE=1", f"-DSPMM_CFG_SIMPLE_TM={tm}"]))
+    out.append(("cfg_slab.o", cfg, ["-DSPMM_CFG_SLAB"]))
     return out
 
 

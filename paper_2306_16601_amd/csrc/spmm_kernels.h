@@ -673,4 +673,134 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
     }
 }
 
+// =======================================================================================
+// Short-batch kernel (token tile 16, K <= 4096): the paper's own regime of 32 to 384 tokens,
+// where a launch is a few microseconds long and its time is memory latency, not throughput.
+// A workgroup (NW row tiles x 16 tokens) requests its whole [K x 16] slab of activations at
+// once and keeps it in LDS (16 bytes per row, no padding: rows whose indices differ mod 16,
+// the packer's order, start in different groups of four banks), so there is one barrier in
+// the kernel and no per-segment round trip to memory.  Each wave then walks all steps of its
+// row tile in one flat loop, its weights arriving through three rotating register sets of
+// CH steps each (the first three sets are requested before the slab is stored).  The segment a
+// step belongs to, which gives the LDS base of its segment-local indices, is tracked with the
+// row tile's segment boundaries held one per lane.
+// =======================================================================================
+constexpr int SLAB_MAX_SEGMENTS = SLAB_SEGMENTS;
+
+template <int NW, int OUT, int POST>
+__global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelArgs a)
+{
+    constexpr int TM = 16, STRIDE = 16, CH = 8;
+    static_assert(NW * 64 == SEGMENT_ROWS, "one thread per activation row of a segment");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[SLAB_MAX_SEGMENTS * SEGMENT_ROWS * STRIDE];
+
+    const int b = blockIdx.x;
+    const int xcd = b & 7, local = b >> 3;
+    const int tt = xcd + 8 * (local / a.n_row_groups);
+    const int rg = local % a.n_row_groups;
+    if (tt >= a.n_tok_tiles) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const int tok0 = tt * TM;
+    const int tile = rg * NW + wave;
+    const bool have_tile = tile < a.ntiles;
+    const int n = tile * TILE_ROWS + c;
+
+    // lane q holds the first step of segment q of this row tile (q = nseg: one past the last step)
+    int bounds = 0;
+    if (have_tile && lane <= a.nseg) bounds = a.seg_ptr[tile * a.nseg + lane];
+
+    // the slab: thread tid fetches row tid of every segment (rows past K repeat the last one;
+    // no step refers to them)
+    v4i xr[SLAB_MAX_SEGMENTS];
+    const bool fast = a.x_vec_ok && tok0 + TM <= a.M;
+#pragma unroll
+    for (int seg = 0; seg < SLAB_MAX_SEGMENTS; ++seg) {
+        if (seg < a.nseg) {
+            const int row = min(seg * SEGMENT_ROWS + tid, a.K - 1);
+            if (fast) xr[seg] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)tok0));
+            else xr[seg] = load_x16(a, row, tok0);
+        }
+    }
+
+    int init = 0;
+    if (have_tile) init = a.rowsum[n] * a.corr_mul;
+    v4i acc = {init, init, init, init};
+    float scale = 0.0f, bias = 0.0f;
+    if constexpr (OUT != SPMM_OUT_S32) {
+        if (have_tile && n < a.N) {
+            scale = a.w_scale[n] * a.x_scale;
+            if (a.bias) bias = a.bias[n];
+        }
+    }
+
+    const int s_begin = __builtin_amdgcn_readlane(bounds, 0);
+    const int s_end = __builtin_amdgcn_readlane(bounds, a.nseg);
+    const int nchunks = (s_end - s_begin + CH - 1) / CH;
+
+    v4i A0[CH], A1[CH], A2[CH];
+    uint32_t I0[CH], I1[CH], I2[CH];
+    auto w_load = [&](const int chunk, v4i (&A)[CH], uint32_t (&I)[CH]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            int step = s_begin + chunk * CH + j;
+            step = (step < s_end) ? step : 0;          // step 0 is always readable
+            A[j] = *(const v4i*)(a.vals + (int64_t)step * STEP_VAL_BYTES + lane * 16);
+            I[j] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
+        }
+    };
+    w_load(0, A0, I0);
+    w_load(1, A1, I1);
+    w_load(2, A2, I2);
+
+#pragma unroll
+    for (int seg = 0; seg < SLAB_MAX_SEGMENTS; ++seg) {
+        if (seg < a.nseg)
+            *(v4i*)(lds + (seg * SEGMENT_ROWS + tid) * STRIDE) = xr[seg] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+    }
+    __syncthreads();
+
+    int seg = 0;
+    int seg_end = __builtin_amdgcn_readlane(bounds, 1);
+    auto multiply = [&](const int chunk, const v4i (&A)[CH], const uint32_t (&I)[CH]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            const int step = s_begin + chunk * CH + j;
+            if (step < s_end) {
+                while (step >= seg_end && seg + 1 < a.nseg) {      // (empty segments are skipped here)
+                    ++seg;
+                    seg_end = __builtin_amdgcn_readlane(bounds, seg + 1);
+                }
+                const uint32_t base = (uint32_t)seg * (SEGMENT_ROWS * STRIDE) + (c & 1) * 8;
+                const uint32_t a0 = (I[j] & 0xffffu) * STRIDE + base;
+                const uint32_t a1 = (I[j] >> 16) * STRIDE + base;
+                const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0));
+                const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1));
+                const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, A[j], acc, 0, 0, 0);
+            }
+        }
+    };
+    for (int ch = 0; ch < nchunks; ch += 3) {
+        multiply(ch, A0, I0);
+        if (ch + 3 < nchunks) w_load(ch + 3, A0, I0);
+        if (ch + 1 < nchunks) {
+            multiply(ch + 1, A1, I1);
+            if (ch + 4 < nchunks) w_load(ch + 4, A1, I1);
+        }
+        if (ch + 2 < nchunks) {
+            multiply(ch + 2, A2, I2);
+            if (ch + 5 < nchunks) w_load(ch + 5, A2, I2);
+        }
+    }
+
+    if (have_tile && n < a.N) {
+        const int m0 = tok0 + 4 * g;
+        if (m0 < a.M) finish4<OUT, POST>(a, acc, scale, bias, n, m0, GlobalLut{a.lut});
+    }
+}
+
 }  // namespace spmm

@@ -21,6 +21,7 @@ SPMM_DECLARE_CFG(launch_cfg_simple_1);
 SPMM_DECLARE_CFG(launch_cfg_simple_2);
 SPMM_DECLARE_CFG(launch_cfg_simple32_1);
 SPMM_DECLARE_CFG(launch_cfg_simple16_1);
+SPMM_DECLARE_CFG(launch_cfg_slab);
 #undef SPMM_DECLARE_CFG
 
 bool plan_supported(int token_tile, int variant)
@@ -28,7 +29,8 @@ bool plan_supported(int token_tile, int variant)
     if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16;
     if (token_tile == 96) return variant == 0 || variant == 16;
     if (token_tile == 64) return variant == 101 || variant == 102;
-    if (token_tile == 32 || token_tile == 16) return variant == 101;
+    if (token_tile == 32) return variant == 101;
+    if (token_tile == 16) return variant == 101 || variant == 103;
     return false;
 }
 
@@ -40,6 +42,7 @@ static void fill_pipelined(Plan& p, int64_t M, int ntiles, int num_cus, int tm, 
     p.waves = waves;
     p.row_tiles_per_wave = 1;
     p.simple = 0;
+    p.slab = 0;
     p.n_tok_tiles = (int)((M + tm - 1) / tm);
     p.n_row_groups = (ntiles + waves - 1) / waves;
     int S = num_cus / p.n_row_groups;
@@ -58,6 +61,7 @@ static void fill_simple(Plan& p, int64_t M, int ntiles, int r, int tm)
     p.waves = 8;
     p.row_tiles_per_wave = r;
     p.simple = 1;
+    p.slab = 0;
     p.n_tok_tiles = (int)((M + tm - 1) / tm);
     p.n_row_groups = (ntiles + p.waves * r - 1) / (p.waves * r);
     p.n_streams = 0;
@@ -78,11 +82,17 @@ static double plan_cost(const Plan& p, int num_cus)
     return (double)rounds * ((double)per_stream * p.token_tile * per_token + 48.0);
 }
 
-Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant)
+Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant, int nseg)
 {
     Plan p{};
     const int max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? max_steps_per_segment : 8);
     p.max_steps = max_steps;
+    if (force_tm == 16 && variant == 103) {
+        // the short-batch kernel holds K <= 4096; longer K silently runs the simple kernel
+        fill_simple(p, M, ntiles, 1, 16);
+        p.slab = nseg <= SLAB_SEGMENTS;
+        return p;
+    }
     if (force_tm == 64 || force_tm == 32 || force_tm == 16) {
         fill_simple(p, M, ntiles, variant - 100, force_tm);
         return p;
@@ -129,6 +139,10 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
                 fill_simple(c, M, ntiles, 1, tm);
                 if ((int64_t)c.n_row_groups * c.n_tok_tiles <= num_cus) p = c;
             }
+            // From five K segments on (K > 2048) the short-batch kernel, which fetches its whole
+            // slab of activations at once, beats the segment-by-segment loop (768x3072, 32 tokens:
+            // 6.4 against 7.3 us); below, its larger fixed cost loses (768x768: 4.9 against 3.8 us).
+            if (p.token_tile == 16 && nseg >= 5 && nseg <= SLAB_SEGMENTS) p.slab = 1;
         }
     }
     return p;
@@ -144,7 +158,10 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop
     if (plan.simple) {
         const unsigned grid = (unsigned)plan.workgroups;
         const int key = plan.token_tile * 10 + plan.row_tiles_per_wave;
-        if (key == 641) launch_cfg_simple_1(out_type, postop, grid, 1, block, stream, a);
+        if (plan.slab) {
+            if (key != 161 || a.nseg > SLAB_SEGMENTS || a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
+            launch_cfg_slab(out_type, postop, grid, 1, block, stream, a);
+        } else if (key == 641) launch_cfg_simple_1(out_type, postop, grid, 1, block, stream, a);
         else if (key == 642) launch_cfg_simple_2(out_type, postop, grid, 1, block, stream, a);
         else if (key == 321) launch_cfg_simple32_1(out_type, postop, grid, 1, block, stream, a);
         else if (key == 161) launch_cfg_simple16_1(out_type, postop, grid, 1, block, stream, a);

@@ -162,6 +162,12 @@ def test_pack_argument_errors():
     assert L.spmm_set_tuning(hh, 0, 8) == sp.SPMM_E_ARG
     assert L.spmm_set_tuning(hh, 64, 0) == sp.SPMM_E_UNSUPPORTED
     assert L.spmm_set_tuning(hh, 64, 102) == sp.SPMM_OK
+    assert L.spmm_set_tuning(hh, 32, 101) == sp.SPMM_OK
+    assert L.spmm_set_tuning(hh, 16, 101) == sp.SPMM_OK
+    assert L.spmm_set_tuning(hh, 32, 102) == sp.SPMM_E_UNSUPPORTED
+    assert L.spmm_set_tuning(hh, 16, 0) == sp.SPMM_E_UNSUPPORTED
+    assert L.spmm_set_tuning(hh, 16, 103) == sp.SPMM_OK
+    assert L.spmm_set_tuning(hh, 32, 103) == sp.SPMM_E_UNSUPPORTED
     assert L.spmm_set_tuning(hh, 96, 16) == sp.SPMM_OK
     assert L.spmm_set_tuning(hh, 96, 8) == sp.SPMM_E_UNSUPPORTED
     assert L.spmm_set_tuning(hh, 0, 0) == sp.SPMM_OK
@@ -233,5 +239,26 @@ def test_plan_picks_token_tile_and_waves_per_shape():
     assert plan(1024, 1024, 6144, 0.9, (128, 8)) == (128, 128, 256)
     assert plan(1024, 1024, 6144, 0.9, (96, 16)) == (96, 256, 256)
     assert plan(256, 256, 128, 0.9, (64, 102))[0] == 64
-    assert plan(768, 768, 128, 0.9) == (64, 128, 48)             # short batch: the simple kernel's many small workgroups
+    assert plan(768, 768, 128, 0.9) == (16, 128, 48)             # short batch: simple kernel, 6 row groups x 8 tiles of 16
+    assert plan(768, 3072, 1024, 0.9) == (32, 128, 192)          # 6 x 32 tiles of 32 still fit the 256 CUs, 6 x 64 do not
+    assert plan(3072, 768, 384, 0.9) == (64, 128, 192)           # 24 row groups: only 64-token tiles fit
+    assert plan(768, 768, 128, 0.9, (32, 101)) == (32, 128, 48)
+    assert plan(768, 768, 128, 0.9, (16, 101)) == (16, 128, 48)
+
+    def kernel(N, K, M, tuning=None):
+        h = sp.spmm_pack_host(wl.sparse_weight(N, K, 0.9, keys=(81, N, K)))
+        try:
+            if tuning:
+                sp.spmm_set_tuning(h, *tuning)
+            return sp.spmm_kernel_variant(h, M, "s8", "gelu")
+        finally:
+            sp.spmm_destroy(h)
+
+    # short batches: the short-batch kernel from five K segments on, up to the eight it holds
+    assert kernel(768, 3072, 128) == "void spmm::spmm_rowtile_mfma_slab<8, 2, 1>(spmm::KernelArgs)"
+    assert kernel(1024, 4096, 32) == "void spmm::spmm_rowtile_mfma_slab<8, 2, 1>(spmm::KernelArgs)"
+    assert kernel(768, 2048, 128) == "void spmm::spmm_rowtile_mfma_simple<16, 8, 1, 2, 1>(spmm::KernelArgs)"
+    assert kernel(768, 4608, 128) == "void spmm::spmm_rowtile_mfma_simple<16, 8, 1, 2, 1>(spmm::KernelArgs)"
+    assert kernel(768, 768, 128, (16, 103)) == "void spmm::spmm_rowtile_mfma_slab<8, 2, 1>(spmm::KernelArgs)"
+    assert kernel(768, 3072, 6144) == "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)"
     assert plan(768, 768, 128, 0.9, (128, 8)) == (128, 128, 6)
