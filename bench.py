@@ -39,8 +39,8 @@ ROTATE = 3   # distinct X/out buffer sets per SpMM (6 calls x 3 sets x ~30 MB > 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size) of the kernel
 # instantiations of the default workload, from the rocprofv3 --pmc runs summarised under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)": 36367058,
-    "void spmm::spmm_rowtile_mfma<96, 16, 6, 2, 1>(spmm::KernelArgs)": 56030864,
+    "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)": 36432848,
+    "void spmm::spmm_rowtile_mfma<96, 16, 6, 2, 1>(spmm::KernelArgs)": 56030404,
 }
 
 
@@ -63,6 +63,8 @@ def main() -> int:
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--tuning", default="", help="token_tile,variant override passed to spmm_set_tuning")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    ap.add_argument("--profile", action="store_true",
+                    help="for profiler runs: warm-up and the event-timed steps only (no graph, no back-to-back loops)")
     ap.add_argument("--only", default="", help="keep only the calls whose case name contains this substring")
     ap.add_argument("--qkv", action="store_true",
                     help="also time the three attention projections (N = K of the first shape) as three launches and "
@@ -149,10 +151,15 @@ def main() -> int:
                           dense_ops=2.0 * N * K * case.M, nnz_ops=2.0 * 4 * nnzb * case.M,
                           plan=sp.spmm_plan(h, case.M, case.out_type)))
 
+    # arguments marshalled once per (call, rotation): a launch is then one C call
+    stream = torch.cuda.current_stream().cuda_stream
+    for c in calls:
+        c["run"] = [sp.spmm_run_bound(c["h"], c["Xs"][j], c["M"], c["M"], c["eps"][j], c["outs"][j], c["M"], stream)
+                    for j in range(ROTATE)]
+
     def launch(c, it):
-        j = it % ROTATE
-        sp.spmm_run(c["h"], c["Xs"][j], c["M"], c["M"], c["eps"][j], c["outs"][j], c["M"],
-                    torch.cuda.current_stream().cuda_stream)
+        if c["run"][it % ROTATE]() != 0:
+            raise RuntimeError("spmm_run failed")
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -192,14 +199,15 @@ def main() -> int:
     # HIP graphs (one graph per buffer rotation; spmm_run allocates nothing and never synchronises, so it
     # captures as is).  Launch-bound sequences of 10-50 us kernels are what graphs are for; this is `value`.
     graph_ms_per_step = None
-    if not args.no_graph:
+    if not args.no_graph and not args.profile:
         try:
             graphs = []
             for j in range(ROTATE):
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g):
+                    cap = torch.cuda.current_stream().cuda_stream      # the capturing stream
                     for c in calls:
-                        launch(c, j)
+                        sp.spmm_run(c["h"], c["Xs"][j], c["M"], c["M"], c["eps"][j], c["outs"][j], c["M"], cap)
                 graphs.append(g)
             for it in range(max(2, args.warmup // 2)):
                 graphs[it % ROTATE].replay()
@@ -213,7 +221,41 @@ def main() -> int:
             graph_ms_per_step = e0.elapsed_time(e1) / args.steps
         except Exception as exc:   # fall back to the eager figure
             print("bench.py: graph capture unavailable (%r); reporting eager launches" % (exc,), file=sys.stderr)
-    ms_per_step = graph_ms_per_step if graph_ms_per_step is not None else eager_ms_per_step
+
+    # ------------------------------------------------------------------ timed region C: the same K steps as plain eager
+    # launches, back to back on the stream with nothing between them.  Kernels of a few microseconds (short
+    # batches) run faster this way than as graph nodes; `value` takes the faster of B and C and says which.
+    stream_ms_per_step = eager_ms_per_step
+    if not args.profile:
+        for it in range(max(2, args.warmup // 2)):
+            for c in calls:
+                launch(c, it)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for it in range(args.steps):
+            for c in calls:
+                launch(c, it)
+        e1.record()
+        torch.cuda.synchronize()
+        stream_ms_per_step = e0.elapsed_time(e1) / args.steps
+    # each call on its own, the same way (what the dense comparator below is timed like)
+    b2b_us = [float(v) for v in avg_us] if args.profile else []
+    for c in ([] if args.profile else calls):
+        for it in range(3):
+            launch(c, it)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for it in range(args.steps):
+            launch(c, it)
+        e1.record()
+        torch.cuda.synchronize()
+        b2b_us.append(e0.elapsed_time(e1) * 1e3 / args.steps)
+    if graph_ms_per_step is not None and graph_ms_per_step <= stream_ms_per_step:
+        ms_per_step, launch_mode = graph_ms_per_step, "hip_graph_replay"
+    else:
+        ms_per_step, launch_mode = stream_ms_per_step, "eager_back_to_back"
 
     dense_ops = sum(c["dense_ops"] for c in calls)
     nnz_ops = sum(c["nnz_ops"] for c in calls)
@@ -304,7 +346,9 @@ def main() -> int:
             "bound": "hbm" if t_hbm >= t_int8 else "mfma", "roofline_frac": round(max(t_hbm, t_int8) / t, 4),
             "nnz_blocks": int(c["nnzb"]), "padded_blocks": int(c["padded"]),
             "plan": {"token_tile": c["plan"][0], "rows_per_wg": c["plan"][1], "workgroups": c["plan"][2]},
-            "speedup_vs_dense_gemm": (round(dense[key]["us"] / t, 2) if key in dense and "us" in dense[key] else None),
+            "us_back_to_back": round(b2b_us[ci], 2),
+            "speedup_vs_dense_gemm": (round(dense[key]["us"] / b2b_us[ci], 2)
+                                      if key in dense and "us" in dense[key] else None),
             "sha256": {"W": wl.sha256(c["d"]["W"])[:16], "X": wl.sha256(c["d"]["X"])[:16]},
         })
     # roofline of the dominant kernel instantiation (largest share of the step): algorithmic bytes of
@@ -374,7 +418,8 @@ def main() -> int:
         "roofline": roofline, "cpu_baseline": cpu, "dense_int8_gemm": dense, "qkv_stacked": qkv, "per_call": rows,
         "ms_per_step_eager_with_events": round(eager_ms_per_step, 5),
         "ms_per_step_graph": (round(graph_ms_per_step, 5) if graph_ms_per_step is not None else None),
-        "launch_mode": ("hip_graph_replay" if graph_ms_per_step is not None else "eager"),
+        "ms_per_step_eager_back_to_back": round(stream_ms_per_step, 5),
+        "launch_mode": launch_mode,
         "host_wall_s_eager": round(wall_s, 4),
     }
     print(json.dumps(line))

@@ -237,6 +237,21 @@ def spmm_run(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, out_dev,
     _check(spmm_run_status(handle, X_dev, M, ldx, ep, out_dev, ldo, stream), "spmm_run")
 
 
+def spmm_run_bound(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, out_dev, ldo: int, stream=None):
+    """spmm_run with its arguments marshalled once: returns a callable that makes the C call and
+    returns its status (for launch loops of microsecond kernels, where converting the arguments
+    every time costs as much as the kernel).  The caller keeps the tensors and `ep` alive."""
+    fn = lib().spmm_run
+    args = (ctypes.c_void_p(handle), ctypes.c_void_p(_dev_ptr(X_dev)), ctypes.c_int64(int(M)), ctypes.c_int64(int(ldx)),
+            ctypes.byref(ep), ctypes.c_void_p(_dev_ptr(out_dev)), ctypes.c_int64(int(ldo)),
+            ctypes.c_void_p(None if stream is None else int(stream)))
+
+    def call() -> int:
+        return fn(*args)
+    call._keepalive = (ep, X_dev, out_dev)
+    return call
+
+
 def spmm_destroy(handle: Optional[int]) -> None:
     if handle:
         lib().spmm_destroy(handle)
