@@ -177,9 +177,10 @@ spmm_status_t spmm_plan(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
  *                   automatic choice for problems too small to fill the chip).
  *   token_tile 32, 16: variant 101 = the simple kernel on narrower token tiles (what the
  *                   automatic choice takes for short batches: more, smaller workgroups).
- *   token_tile  16: variant 103 = the short-batch kernel, which keeps a workgroup's whole
- *                   [K x 16] slab of activations in LDS (K <= 4096; a longer K silently runs
- *                   variant 101).  The automatic choice for short batches with 2048 < K <= 4096:
+ *   token_tile 16, 32: variant 103 = the short-batch kernel, which keeps a workgroup's whole
+ *                   [K x token_tile] slab of activations in LDS (K <= 4096 with 16-token tiles,
+ *                   K <= 3072 with 32; a longer K silently runs variant 101).  The automatic
+ *                   choice for short batches with 2048 < K <= 4096:
  *                   Section 4.3 measures the kernels at 32 tokens and the models at sequence
  *                   lengths of 16 to 384.
  * Unsupported values return SPMM_E_UNSUPPORTED and change nothing.  Not thread-safe against

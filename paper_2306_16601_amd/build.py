@@ -21,6 +21,7 @@ HOST_SOURCES = ["api.cpp", "pack.cpp", "spmm_plan.hip"]
 PIPELINED = [(128, 16, 4), (128, 16, 5), (128, 16, 6), (128, 8, 4), (128, 8, 6), (128, 8, 8),
              (96, 16, 4), (96, 16, 5), (96, 16, 6)]
 SIMPLE = [1, 2]
+SLAB = [16, 32]            # token tiles of the short-batch kernel
 SIMPLE_NARROW = [32, 16]   # token tiles of the simple kernel besides 64 (one row tile per wave)
 HEADERS = [os.path.join(CSRC, "spmm_internal.h"), os.path.join(CSRC, "spmm_kernels.h"),
            os.path.join(ROOT, "include", "spmm.h")]
@@ -44,7 +45,8 @@ def units():
         out.append((f"cfg_simple_{r}.o", cfg, [f"-DSPMM_CFG_SIMPLE={r}"]))
     for tm in SIMPLE_NARROW:
         out.append((f"cfg_simple{tm}_1.o", cfg, ["-DSPMM_CFG_SIMPLE=1", f"-DSPMM_CFG_SIMPLE_TM={tm}"]))
-    out.append(("cfg_slab.o", cfg, ["-DSPMM_CFG_SLAB"]))
+    for tm in SLAB:
+        out.append((f"cfg_slab{tm}.o", cfg, [f"-DSPMM_CFG_SLAB={tm}"]))
     return out
 
 

@@ -274,8 +274,8 @@ spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t 
     const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r, h->nseg);
     const int post = (out_type == SPMM_OUT_S32) ? 0 : (int)postop;   // S32 output ignores the post-operator
     if (p.slab)
-        std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_slab<%d, %d, %d>(spmm::KernelArgs)", p.waves,
-                      (int)out_type, post);
+        std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_slab<%d, %d, %d, %d>(spmm::KernelArgs)",
+                      p.token_tile, p.waves, (int)out_type, post);
     else if (p.simple)
         std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_simple<%d, %d, %d, %d, %d>(spmm::KernelArgs)",
                       p.token_tile, p.waves, p.row_tiles_per_wave, (int)out_type, post);

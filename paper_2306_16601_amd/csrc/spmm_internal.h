@@ -91,7 +91,7 @@ struct Plan {
     int row_tiles_per_wave;  // 1 (pipelined) or 1 / 2 (simple kernel)
     int waves;               // NW
     int simple;              // 1: simple kernel
-    int slab;                // 1: the short-batch kernel (token tile 16, whole K resident in LDS) in its place
+    int slab;                // 1: the short-batch kernel (token tile 16 or 32, whole K resident in LDS) in its place
     int max_steps;           // unroll bound of the per-segment step loop (pipelined kernel)
     int n_row_groups, n_tok_tiles, n_streams, xcd_map;
     int64_t workgroups;
@@ -99,8 +99,9 @@ struct Plan {
 
 // variant: 0 = automatic, 8 / 16 = waves per workgroup (pipelined, token tile 128 or 96),
 // 101 / 102 = simple kernel with 1 / 2 row tiles per wave (token tile 64; 101 also 32 and 16),
-// 103 = short-batch kernel (token tile 16)
-constexpr int SLAB_SEGMENTS = 8;   // K segments the short-batch kernel keeps in LDS
+// 103 = short-batch kernel (token tile 16 or 32)
+constexpr int SLAB_SEGMENTS = 8;      // K segments the short-batch kernel keeps in LDS, token tile 16
+constexpr int SLAB_SEGMENTS_32 = 6;   // and token tile 32
 bool plan_supported(int token_tile, int variant);
 Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant, int nseg);
 // Launches the SpMM kernel; returns a hipError_t value as int (0 = success).

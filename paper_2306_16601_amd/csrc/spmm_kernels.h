@@ -674,25 +674,27 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
 }
 
 // =======================================================================================
-// Short-batch kernel (token tile 16, K <= 4096): the paper's own regime of 32 to 384 tokens,
+// Short-batch kernel (token tile 16 with K <= 4096, or 32 with K <= 3072): the paper's own regime of 32 to 384 tokens,
 // where a launch is a few microseconds long and its time is memory latency, not throughput.
-// A workgroup (NW row tiles x 16 tokens) requests its whole [K x 16] slab of activations at
-// once and keeps it in LDS (16 bytes per row, no padding: rows whose indices differ mod 16,
-// the packer's order, start in different groups of four banks), so there is one barrier in
+// A workgroup (NW row tiles x TM tokens) requests its whole [K x TM] slab of activations at
+// once and keeps it in LDS (TM = 16: 16 bytes per row, no padding: rows whose indices differ mod
+// 16, the packer's order, start in different groups of four banks), so there is one barrier in
 // the kernel and no per-segment round trip to memory.  Each wave then walks all steps of its
 // row tile in one flat loop, its weights arriving through three rotating register sets of
 // CH steps each (the first three sets are requested before the slab is stored).  The segment a
 // step belongs to, which gives the LDS base of its segment-local indices, is tracked with the
 // row tile's segment boundaries held one per lane.
 // =======================================================================================
-constexpr int SLAB_MAX_SEGMENTS = SLAB_SEGMENTS;
-
-template <int NW, int OUT, int POST>
+// TM = 16: 16 bytes per row, up to SLAB_SEGMENTS segments (64 KB).  TM = 32: 48 bytes per row (the
+// pitch of the simple kernel's 32-token tile), up to SLAB_SEGMENTS_32 segments (144 KB).
+template <int TM, int NW, int OUT, int POST>
 __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelArgs a)
 {
-    constexpr int TM = 16, STRIDE = 16, CH = 8;
+    static_assert(TM == 16 || TM == 32, "token tile of the short-batch kernel");
+    constexpr int STRIDE = (TM == 16) ? 16 : 48, PIECES = TM / 16, CH = 8;
+    constexpr int SEGS = (TM == 16) ? SLAB_SEGMENTS : SLAB_SEGMENTS_32;
     static_assert(NW * 64 == SEGMENT_ROWS, "one thread per activation row of a segment");
-    __shared__ __attribute__((aligned(16))) uint8_t lds[SLAB_MAX_SEGMENTS * SEGMENT_ROWS * STRIDE];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[SEGS * SEGMENT_ROWS * STRIDE];
 
     const int b = blockIdx.x;
     const int xcd = b & 7, local = b >> 3;
@@ -713,22 +715,28 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
     int bounds = 0;
     if (have_tile && lane <= a.nseg) bounds = a.seg_ptr[tile * a.nseg + lane];
 
-    // the slab: thread tid fetches row tid of every segment (rows past K repeat the last one;
-    // no step refers to them)
-    v4i xr[SLAB_MAX_SEGMENTS];
+    // the slab: PIECES 16-byte pieces per thread and segment (rows past K repeat the last one; no
+    // step refers to them)
+    v4i xr[SEGS][PIECES];
     const bool fast = a.x_vec_ok && tok0 + TM <= a.M;
 #pragma unroll
-    for (int seg = 0; seg < SLAB_MAX_SEGMENTS; ++seg) {
+    for (int seg = 0; seg < SEGS; ++seg) {
         if (seg < a.nseg) {
-            const int row = min(seg * SEGMENT_ROWS + tid, a.K - 1);
-            if (fast) xr[seg] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)tok0));
-            else xr[seg] = load_x16(a, row, tok0);
+#pragma unroll
+            for (int u = 0; u < PIECES; ++u) {
+                const int p = tid + u * NW * 64;
+                const int row = min(seg * SEGMENT_ROWS + p / PIECES, a.K - 1), col = tok0 + (p % PIECES) * 16;
+                if (fast) xr[seg][u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)col));
+                else xr[seg][u] = load_x16(a, row, col);
+            }
         }
     }
 
     int init = 0;
     if (have_tile) init = a.rowsum[n] * a.corr_mul;
-    v4i acc = {init, init, init, init};
+    v4i acc[PIECES];
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
     float scale = 0.0f, bias = 0.0f;
     if constexpr (OUT != SPMM_OUT_S32) {
         if (have_tile && n < a.N) {
@@ -757,9 +765,15 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
     w_load(2, A2, I2);
 
 #pragma unroll
-    for (int seg = 0; seg < SLAB_MAX_SEGMENTS; ++seg) {
-        if (seg < a.nseg)
-            *(v4i*)(lds + (seg * SEGMENT_ROWS + tid) * STRIDE) = xr[seg] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+    for (int seg = 0; seg < SEGS; ++seg) {
+        if (seg < a.nseg) {
+#pragma unroll
+            for (int u = 0; u < PIECES; ++u) {
+                const int p = tid + u * NW * 64;
+                *(v4i*)(lds + (seg * SEGMENT_ROWS + p / PIECES) * STRIDE + (p % PIECES) * 16) =
+                    xr[seg][u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+            }
+        }
     }
     __syncthreads();
 
@@ -777,10 +791,13 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
                 const uint32_t base = (uint32_t)seg * (SEGMENT_ROWS * STRIDE) + (c & 1) * 8;
                 const uint32_t a0 = (I[j] & 0xffffu) * STRIDE + base;
                 const uint32_t a1 = (I[j] >> 16) * STRIDE + base;
-                const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0));
-                const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1));
-                const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, A[j], acc, 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < PIECES; ++i) {
+                    const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0 + 16 * i));
+                    const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1 + 16 * i));
+                    const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
+                    acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, A[j], acc[i], 0, 0, 0);
+                }
             }
         }
     };
@@ -798,8 +815,11 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
     }
 
     if (have_tile && n < a.N) {
-        const int m0 = tok0 + 4 * g;
-        if (m0 < a.M) finish4<OUT, POST>(a, acc, scale, bias, n, m0, GlobalLut{a.lut});
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) {
+            const int m0 = tok0 + 16 * i + 4 * g;
+            if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, GlobalLut{a.lut});
+        }
     }
 }
 

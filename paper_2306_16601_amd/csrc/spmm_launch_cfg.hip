@@ -3,7 +3,7 @@
 //   pipelined kernel : -DSPMM_CFG_TM=<128|96> -DSPMM_CFG_NW=<16|8> -DSPMM_CFG_MAXS=<4|5|6|8>
 //   simple kernel    : -DSPMM_CFG_SIMPLE=<1|2>      (row tiles per wave; token tile 64)
 //                      -DSPMM_CFG_SIMPLE=1 -DSPMM_CFG_SIMPLE_TM=<32|16>
-//   short-batch kernel: -DSPMM_CFG_SLAB
+//   short-batch kernel: -DSPMM_CFG_SLAB=<16|32>      (token tile)
 // Each defines one function launch_cfg_<...>() that picks the epilogue instantiation and
 // launches it; spmm_plan.hip calls them.
 #include "spmm_kernels.h"
@@ -47,11 +47,11 @@ struct SlabLaunch {
     template <int OUT, int POST>
     static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
     {
-        hipLaunchKernelGGL((spmm_rowtile_mfma_slab<8, OUT, POST>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((spmm_rowtile_mfma_slab<SPMM_CFG_SLAB, 8, OUT, POST>), grid, block, 0, st, a);
     }
 };
 
-void launch_cfg_slab(spmm_out_t out_type, int postop, unsigned grid_x, unsigned grid_y, unsigned block, void* stream,
+void SPMM_CAT(launch_cfg_slab, SPMM_CFG_SLAB)(spmm_out_t out_type, int postop, unsigned grid_x, unsigned grid_y, unsigned block, void* stream,
                      const KernelArgs& a)
 {
     dispatch_epilogue<SlabLaunch>(out_type, postop, dim3(grid_x, grid_y), dim3(block), (hipStream_t)stream, a);

@@ -21,7 +21,8 @@ SPMM_DECLARE_CFG(launch_cfg_simple_1);
 SPMM_DECLARE_CFG(launch_cfg_simple_2);
 SPMM_DECLARE_CFG(launch_cfg_simple32_1);
 SPMM_DECLARE_CFG(launch_cfg_simple16_1);
-SPMM_DECLARE_CFG(launch_cfg_slab);
+SPMM_DECLARE_CFG(launch_cfg_slab16);
+SPMM_DECLARE_CFG(launch_cfg_slab32);
 #undef SPMM_DECLARE_CFG
 
 bool plan_supported(int token_tile, int variant)
@@ -29,8 +30,7 @@ bool plan_supported(int token_tile, int variant)
     if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16;
     if (token_tile == 96) return variant == 0 || variant == 16;
     if (token_tile == 64) return variant == 101 || variant == 102;
-    if (token_tile == 32) return variant == 101;
-    if (token_tile == 16) return variant == 101 || variant == 103;
+    if (token_tile == 32 || token_tile == 16) return variant == 101 || variant == 103;
     return false;
 }
 
@@ -87,10 +87,11 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
     Plan p{};
     const int max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? max_steps_per_segment : 8);
     p.max_steps = max_steps;
-    if (force_tm == 16 && variant == 103) {
-        // the short-batch kernel holds K <= 4096; longer K silently runs the simple kernel
-        fill_simple(p, M, ntiles, 1, 16);
-        p.slab = nseg <= SLAB_SEGMENTS;
+    if ((force_tm == 16 || force_tm == 32) && variant == 103) {
+        // the short-batch kernel holds K <= 4096 (3072 with 32-token tiles); longer K silently runs
+        // the simple kernel
+        fill_simple(p, M, ntiles, 1, force_tm);
+        p.slab = nseg <= (force_tm == 16 ? SLAB_SEGMENTS : SLAB_SEGMENTS_32);
         return p;
     }
     if (force_tm == 64 || force_tm == 32 || force_tm == 16) {
@@ -143,6 +144,8 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
             // slab of activations at once, beats the segment-by-segment loop (768x3072, 32 tokens:
             // 6.4 against 7.3 us); below, its larger fixed cost loses (768x768: 4.9 against 3.8 us).
             if (p.token_tile == 16 && nseg >= 5 && nseg <= SLAB_SEGMENTS) p.slab = 1;
+            // (32-token tiles, 768x3072, 1024 tokens: 9.7 against 10.5 us; at 70 %: 13.1 against 13.8 us)
+            if (p.token_tile == 32 && nseg >= 5 && nseg <= SLAB_SEGMENTS_32) p.slab = 1;
         }
     }
     return p;
@@ -159,8 +162,10 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop
         const unsigned grid = (unsigned)plan.workgroups;
         const int key = plan.token_tile * 10 + plan.row_tiles_per_wave;
         if (plan.slab) {
-            if (key != 161 || a.nseg > SLAB_SEGMENTS || a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
-            launch_cfg_slab(out_type, postop, grid, 1, block, stream, a);
+            if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
+            if (key == 161 && a.nseg <= SLAB_SEGMENTS) launch_cfg_slab16(out_type, postop, grid, 1, block, stream, a);
+            else if (key == 321 && a.nseg <= SLAB_SEGMENTS_32) launch_cfg_slab32(out_type, postop, grid, 1, block, stream, a);
+            else return (int)hipErrorInvalidValue;
         } else if (key == 641) launch_cfg_simple_1(out_type, postop, grid, 1, block, stream, a);
         else if (key == 642) launch_cfg_simple_2(out_type, postop, grid, 1, block, stream, a);
         else if (key == 321) launch_cfg_simple32_1(out_type, postop, grid, 1, block, stream, a);
