@@ -48,14 +48,79 @@ def algorithmic_bytes(N, K, M, nnz_blocks, out_elem):
     return K * M + N * M * out_elem + 6 * nnz_blocks + 4 * (N // 4 + 1) + 12 * N
 
 
+def run_grid(args, np, torch, sp, wl) -> int:
+    """The kernel benchmark the paper reports as geometric means over its GEMM shapes (Section 5.1 and its
+    table of sparse-against-dense speed-ups per sparsity ratio): every case of the 92-shape grid, one at a time, as a back-to-back loop of `steps` launches of
+    the sparse kernel (int8 requantised output) and of the dense int8 GEMM of the same shape."""
+    import math
+    sps = tuple(float(v) for v in args.sparsities.split(",")) if args.sparsities else wl.SPARSITIES
+    Ms = (args.tokens,) if args.tokens else wl.GRID_M
+    cases = wl.grid_cases(out_type="s8", sparsities=sps, Ms=Ms)
+    if args.only:
+        cases = [c for c in cases if args.only in c.name]
+    stream = torch.cuda.current_stream().cuda_stream
+    steps = max(5, args.steps)
+
+    def loop_us(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / steps
+
+    dense_us, rows = {}, []
+    ops = t_sparse = 0.0
+    for case in cases:
+        d = wl.make(case)
+        h = sp.spmm_pack(d["W"], case.orientation)
+        ws, bias, X = (torch.from_numpy(d[k]).cuda() for k in ("w_scale", "bias", "X"))
+        out = torch.empty((case.N, case.M), dtype=torch.int8, device="cuda")
+        ep = sp.make_epilogue(ws, d["x_scale"], 0, bias, "none", "s8", d["out_scale"], 0)
+        us = loop_us(sp.spmm_run_bound(h, X, case.M, case.M, ep, out, case.M, stream))
+        key = (case.N, case.K, case.M)
+        if key not in dense_us and not args.no_dense:
+            a = torch.randint(-128, 127, (case.M, case.K), dtype=torch.int8, device="cuda")
+            b = torch.randint(-128, 127, (case.N, case.K), dtype=torch.int8, device="cuda").t()
+            dense_us[key] = loop_us(lambda: torch._int_mm(a, b))
+        sp.spmm_destroy(h)
+        ops += 2.0 * case.N * case.K * case.M
+        t_sparse += us
+        rows.append((case, us, dense_us.get(key)))
+    table = {}
+    for s in sps:
+        for M in Ms:
+            r = [dn / us for c, us, dn in rows if c.sparsity == s and c.M == M and dn]
+            if r:
+                table.setdefault("s%d" % round(s * 100), {})["m%d" % M] = {
+                    "geomean": round(math.exp(sum(math.log(v) for v in r) / len(r)), 2),
+                    "min": round(min(r), 2), "max": round(max(r), 2), "shapes": len(r)}
+    print(json.dumps({
+        "metric": "SpMM dense-equivalent TOPS (4x1 block-sparse INT8, BERT shapes, fused epilogue)",
+        "value": round(ops / t_sparse / 1e6, 2), "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": 3,
+        "ms_per_step": round(t_sparse / 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "shape_grid_%d_cases_s8" % len(rows), "launch_mode": "eager_back_to_back"},
+        "speedup_vs_dense_gemm": table,
+        "slowest_vs_dense": [{"case": c.name, "us": round(us, 2), "dense_us": round(dn, 2)}
+                             for c, us, dn in sorted([r for r in rows if r[2]], key=lambda r: r[2] / r[1])[:5]],
+    }))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "large_sum"],
+    ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "large_sum", "grid"],
                     help="large_sum: the two BERT-Large Linears that feed a residual add (attention output and "
-                         "second feed-forward), with the Sum post-operator and fp32 output")
+                         "second feed-forward), with the Sum post-operator and fp32 output; grid: the 92-shape grid "
+                         "(int8 output), geometric-mean speed-up over the dense int8 GEMM per sparsity and token count")
     ap.add_argument("--tokens", type=int, default=0,
                     help="workload base only: token count M (default 4096 = 32 sequences of 128)")
     ap.add_argument("--sparsities", default="", help="workload base only: comma list, e.g. 0.7,0.8,0.9")
@@ -90,6 +155,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
 
+    if args.workload == "grid":
+        return run_grid(args, np, torch, sp, wl)
     if args.workload == "large":
         cases = wl.large_cases()
         wname = "bert_large_layers_m6144_s90_s80_gelu_s8"

@@ -54,6 +54,13 @@ void free_device(spmm_handle* h)
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+spmm::Plan plan_for(const spmm_handle* h, int64_t M)
+{
+    const spmm::WeightDims w{h->ntiles, h->nseg, (int)h->bsr.K, h->nsteps, h->max_steps_per_segment,
+                             h->max_steps_per_tile};
+    return spmm::make_plan(M, w, h->num_cus, h->force_tm, h->force_r);
+}
+
 }  // namespace
 
 extern "C" {
@@ -164,7 +171,7 @@ spmm_status_t spmm_plan(const spmm_handle_t* h, int64_t M, spmm_out_t out_type, 
                         int32_t* rows_per_workgroup, int64_t* workgroups)
 {
     if (!h || M <= 0) return SPMM_E_ARG;
-    const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r, h->nseg);
+    const spmm::Plan p = plan_for(h, M);
     if (token_tile) *token_tile = p.token_tile;
     if (rows_per_workgroup) *rows_per_workgroup = p.waves * p.row_tiles_per_wave * spmm::TILE_ROWS;
     (void)out_type;
@@ -238,7 +245,7 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
                        (h->bsr.N * ep->ld_sum * 4 < ((int64_t)1 << 31));
     }
 
-    const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r, h->nseg);
+    const spmm::Plan p = plan_for(h, M);
     const int rc = spmm::launch_spmm(p, a, ot, (gelu ? SPMM_POST_GELU : SPMM_POST_NONE) | (ep->sum ? spmm::POST_SUM_BIT : 0),
                                      hip_stream);
     return rc == 0 ? SPMM_OK : SPMM_E_DEVICE;
@@ -271,7 +278,7 @@ spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t 
     if (out_type < SPMM_OUT_S32 || out_type > SPMM_OUT_U8) return SPMM_E_ARG;
     if (postop != SPMM_POST_NONE && postop != SPMM_POST_GELU && postop != SPMM_POST_TABLE) return SPMM_E_ARG;
     if (postop == SPMM_POST_TABLE) postop = SPMM_POST_GELU;   // same kernels
-    const spmm::Plan p = spmm::make_plan(M, h->ntiles, h->max_steps_per_segment, h->num_cus, h->force_tm, h->force_r, h->nseg);
+    const spmm::Plan p = plan_for(h, M);
     const int post = (out_type == SPMM_OUT_S32) ? 0 : (int)postop;   // S32 output ignores the post-operator
     if (p.slab)
         std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_slab<%d, %d, %d, %d>(spmm::KernelArgs)",

@@ -78,7 +78,7 @@ struct KernelArgs {
     int n_tok_tiles, n_row_groups;
     int n_streams;       // persistent kernel: workgroups per row group, each walking token tiles j*n_streams + stream
     int tiles_per_stream, tiles_extra;   // n_tok_tiles = tiles_per_stream * n_streams + tiles_extra
-    int xcd_map;         // simple kernel only: 1 = workgroup ids decoded so that a token tile stays on one XCD
+    int xcd_map;         // simple / short-batch kernels: how a workgroup id decodes, see decode_workgroup()
     int corr_mul;        // 128 - x_zero_point: the activations are multiplied as (x - 128)
     float x_scale, inv_out, inv_mid, out_zp_f;
     int x_vec_ok;        // X base 16-byte aligned, ldx % 16 == 0 and K * ldx < 2^31
@@ -102,8 +102,14 @@ struct Plan {
 // 103 = short-batch kernel (token tile 16 or 32)
 constexpr int SLAB_SEGMENTS = 8;      // K segments the short-batch kernel keeps in LDS, token tile 16
 constexpr int SLAB_SEGMENTS_32 = 6;   // and token tile 32
+// what the plan needs to know of a packed weight
+struct WeightDims {
+    int ntiles, nseg, K;
+    int64_t nsteps;
+    int max_steps_per_segment, max_steps_per_tile;
+};
 bool plan_supported(int token_tile, int variant);
-Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant, int nseg);
+Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant);
 // Launches the SpMM kernel; returns a hipError_t value as int (0 = success).
 // postop: SPMM_POST_* value, plus POST_SUM_BIT when a.sum is to be added
 constexpr int POST_SUM_BIT = 2;

@@ -537,6 +537,22 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     }
 }
 
+// Workgroup id -> (token tile, row group) of the simple and short-batch kernels.  Ids go round the
+// 8 XCDs; map 1 keeps the workgroups of a token tile on one XCD, map 2 those of a row group (the
+// host picks the one that slices the larger operand over the L2s).  False: a padding workgroup.
+__device__ __forceinline__ bool decode_workgroup(const KernelArgs& a, const int b, int& tt, int& rg)
+{
+    const int xcd = b & 7, local = b >> 3;
+    if (a.xcd_map == 2) {
+        rg = xcd + 8 * (local / a.n_tok_tiles);
+        tt = local % a.n_tok_tiles;
+        return rg < a.n_row_groups;
+    }
+    tt = xcd + 8 * (local / a.n_row_groups);
+    rg = local % a.n_row_groups;
+    return tt < a.n_tok_tiles;
+}
+
 // =======================================================================================
 // Simple kernel (token tile 64, 32 or 16, one K segment in LDS, no software pipelining, table
 // read from global memory): an independent second implementation of the same layout, selected
@@ -555,11 +571,8 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
     static_assert(TM == 64 || TM == 32 || TM == 16, "token tile of the simple kernel");
     __shared__ __attribute__((aligned(16))) uint8_t lds[SEGMENT_ROWS * STRIDE];
 
-    const int b = blockIdx.x;
-    const int xcd = b & 7, local = b >> 3;
-    const int tt = xcd + 8 * (local / a.n_row_groups);
-    const int rg = local % a.n_row_groups;
-    if (tt >= a.n_tok_tiles) return;
+    int tt, rg;
+    if (!decode_workgroup(a, blockIdx.x, tt, rg)) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -696,11 +709,8 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
     static_assert(NW * 64 == SEGMENT_ROWS, "one thread per activation row of a segment");
     __shared__ __attribute__((aligned(16))) uint8_t lds[SEGS * SEGMENT_ROWS * STRIDE];
 
-    const int b = blockIdx.x;
-    const int xcd = b & 7, local = b >> 3;
-    const int tt = xcd + 8 * (local / a.n_row_groups);
-    const int rg = local % a.n_row_groups;
-    if (tt >= a.n_tok_tiles) return;
+    int tt, rg;
+    if (!decode_workgroup(a, blockIdx.x, tt, rg)) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;

@@ -55,8 +55,12 @@ static void fill_pipelined(Plan& p, int64_t M, int ntiles, int num_cus, int tm, 
 }
 
 // Simple kernel: tm-token tiles, 8 waves with r row tiles each, one workgroup per (row group, tile).
-static void fill_simple(Plan& p, int64_t M, int ntiles, int r, int tm)
+// Workgroup ids go round the 8 XCDs; which of the two operands an XCD's L2 then holds a slice of:
+// map 1 keeps a token tile on one XCD (every XCD reads all of W), map 2 keeps a row group on one
+// XCD (every XCD reads all of X): whichever operand is the larger is the one that is sliced.
+static void fill_simple(Plan& p, int64_t M, const WeightDims& w, int r, int tm)
 {
+    const int ntiles = w.ntiles;
     p.token_tile = tm;
     p.waves = 8;
     p.row_tiles_per_wave = r;
@@ -65,8 +69,10 @@ static void fill_simple(Plan& p, int64_t M, int ntiles, int r, int tm)
     p.n_tok_tiles = (int)((M + tm - 1) / tm);
     p.n_row_groups = (ntiles + p.waves * r - 1) / (p.waves * r);
     p.n_streams = 0;
-    p.xcd_map = 1;
-    p.workgroups = (int64_t)8 * p.n_row_groups * ((p.n_tok_tiles + 7) / 8);
+    const int64_t w_bytes = w.nsteps * (STEP_VAL_BYTES + 4 * STEP_IDX_DWORDS), x_bytes = (int64_t)w.K * M;
+    p.xcd_map = (w_bytes > x_bytes) ? 2 : 1;
+    p.workgroups = (p.xcd_map == 2) ? (int64_t)8 * ((p.n_row_groups + 7) / 8) * p.n_tok_tiles
+                                    : (int64_t)8 * p.n_row_groups * ((p.n_tok_tiles + 7) / 8);
 }
 
 // Relative duration of a plan: the longest stream's tokens times what a token costs a workgroup
@@ -82,20 +88,21 @@ static double plan_cost(const Plan& p, int num_cus)
     return (double)rounds * ((double)per_stream * p.token_tile * per_token + 48.0);
 }
 
-Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, int force_tm, int variant, int nseg)
+Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant)
 {
+    const int ntiles = w.ntiles, nseg = w.nseg, max_steps_per_segment = w.max_steps_per_segment;
     Plan p{};
     const int max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? max_steps_per_segment : 8);
     p.max_steps = max_steps;
     if ((force_tm == 16 || force_tm == 32) && variant == 103) {
         // the short-batch kernel holds K <= 4096 (3072 with 32-token tiles); longer K silently runs
         // the simple kernel
-        fill_simple(p, M, ntiles, 1, force_tm);
+        fill_simple(p, M, w, 1, force_tm);
         p.slab = nseg <= (force_tm == 16 ? SLAB_SEGMENTS : SLAB_SEGMENTS_32);
         return p;
     }
     if (force_tm == 64 || force_tm == 32 || force_tm == 16) {
-        fill_simple(p, M, ntiles, variant - 100, force_tm);
+        fill_simple(p, M, w, variant - 100, force_tm);
         return p;
     }
     // 16 waves have 128 registers each: at most 6 steps per segment; denser weights run with 8
@@ -130,14 +137,14 @@ Plan make_plan(int64_t M, int ntiles, int max_steps_per_segment, int num_cus, in
         // the faster one there (768x768, 128..1024 tokens: 5.8-6.0 us against 7.5-7.9 us).
         Plan c{};
         c.max_steps = max_steps;
-        fill_simple(c, M, ntiles, 1, 64);
+        fill_simple(c, M, w, 1, 64);
         if ((int64_t)c.n_row_groups * c.n_tok_tiles >= p.workgroups) {   // (its grid is padded to the XCDs)
             p = c;
             // A simple-kernel workgroup is bound by its own CU's LDS (8 waves gathering from one
             // staged segment), so while CUs are idle, narrower token tiles on more CUs finish
             // sooner: the narrowest tile that still gives every workgroup a CU of its own.
             for (int tm = 32; tm >= 16; tm /= 2) {
-                fill_simple(c, M, ntiles, 1, tm);
+                fill_simple(c, M, w, 1, tm);
                 if ((int64_t)c.n_row_groups * c.n_tok_tiles <= num_cus) p = c;
             }
             // From five K segments on (K > 2048) the short-batch kernel, which fetches its whole

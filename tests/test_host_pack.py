@@ -240,11 +240,13 @@ def test_plan_picks_token_tile_and_waves_per_shape():
     assert plan(1024, 1024, 6144, 0.9, (128, 8)) == (128, 128, 256)
     assert plan(1024, 1024, 6144, 0.9, (96, 16)) == (96, 256, 256)
     assert plan(256, 256, 128, 0.9, (64, 102))[0] == 64
-    assert plan(768, 768, 128, 0.9) == (16, 128, 48)             # short batch: simple kernel, 6 row groups x 8 tiles of 16
+    # short batch: simple kernel, 6 row groups x 8 tiles of 16; the packed weight is larger than X, so a row
+    # group's workgroups share an XCD and the grid is padded to 8 row groups
+    assert plan(768, 768, 128, 0.9) == (16, 128, 64)
     assert plan(768, 3072, 1024, 0.9) == (32, 128, 192)          # 6 x 32 tiles of 32 still fit the 256 CUs, 6 x 64 do not
-    assert plan(3072, 768, 384, 0.9) == (64, 128, 192)           # 24 row groups: only 64-token tiles fit
-    assert plan(768, 768, 128, 0.9, (32, 101)) == (32, 128, 48)
-    assert plan(768, 768, 128, 0.9, (16, 101)) == (16, 128, 48)
+    assert plan(3072, 768, 384, 0.9) == (64, 128, 144)           # 24 row groups: only 64-token tiles fit (24 x 6)
+    assert plan(768, 768, 128, 0.9, (32, 101)) == (32, 128, 32)
+    assert plan(768, 768, 128, 0.9, (16, 101)) == (16, 128, 64)
 
     def kernel(N, K, M, tuning=None):
         h = sp.spmm_pack_host(wl.sparse_weight(N, K, 0.9, keys=(81, N, K)))
