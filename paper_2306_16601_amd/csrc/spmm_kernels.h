@@ -330,7 +330,9 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     // workgroup -> (token-tile stream, row group) = (blockIdx.x, blockIdx.y).  Workgroups go to the
     // 8 XCDs round-robin in linear order (x fastest); the host makes gridDim.x a multiple of 8
     // whenever it can, so that all row groups of one stream run on the same XCD and share its L2.
-    const int stream = blockIdx.x, rg = blockIdx.y;
+    // With xcd_map 2 the two roles are swapped (all streams of a row group on one XCD): the host's
+    // choice when the packed weight is the larger operand.
+    const int stream = (a.xcd_map == 2) ? blockIdx.y : blockIdx.x, rg = (a.xcd_map == 2) ? blockIdx.x : blockIdx.y;
     const int S = a.n_streams;
     const int n_my = a.tiles_per_stream + (stream < a.tiles_extra ? 1 : 0);   // token tiles of this stream (>= 1)
     const int total = n_my * a.nseg;                                          // phases

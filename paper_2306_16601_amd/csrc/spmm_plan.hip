@@ -155,6 +155,12 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
             if (p.token_tile == 32 && nseg >= 5 && nseg <= SLAB_SEGMENTS_32) p.slab = 1;
         }
     }
+    if (!p.simple) {
+        // the same choice of the sliced operand as for the simple kernel (fill_simple): all
+        // streams of a row group on one XCD when the packed weight is larger than X
+        const int64_t w_bytes = w.nsteps * (STEP_VAL_BYTES + 4 * STEP_IDX_DWORDS), x_bytes = (int64_t)w.K * M;
+        if (w_bytes > x_bytes && p.n_row_groups % 8 == 0) p.xcd_map = 2;
+    }
     return p;
 }
 
@@ -182,7 +188,8 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop
     }
     if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
     // 2-D grid: x = token-tile stream, y = row group
-    const unsigned gx = (unsigned)plan.n_streams, gy = (unsigned)plan.n_row_groups;
+    unsigned gx = (unsigned)plan.n_streams, gy = (unsigned)plan.n_row_groups;
+    if (plan.xcd_map == 2) { gx = (unsigned)plan.n_row_groups; gy = (unsigned)plan.n_streams; }
     a.tiles_per_stream = plan.n_tok_tiles / plan.n_streams;
     a.tiles_extra = plan.n_tok_tiles % plan.n_streams;
     const int maxs = (plan.waves == 8 && plan.max_steps == 5) ? 6 : plan.max_steps;   // no 8-wave 5-step build
