@@ -183,6 +183,10 @@ spmm_status_t spmm_plan(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
  *                   choice for short batches with 2048 < K <= 4096:
  *                   Section 4.3 measures the kernels at 32 tokens and the models at sequence
  *                   lengths of 16 to 384.
+ *   token_tile 64, 32, 16: variant 104 = the streamed kernel: the simple kernel's segment by
+ *                   segment staging with the weights arriving through rotating register sets
+ *                   (the automatic choice for short batches from seven K segments on, K > 3072,
+ *                   where the short-batch kernel does not apply).
  * Unsupported values return SPMM_E_UNSUPPORTED and change nothing.  Not thread-safe against
  * concurrent spmm_run on the same handle. */
 spmm_status_t spmm_set_tuning(spmm_handle_t *h, int32_t token_tile, int32_t variant);

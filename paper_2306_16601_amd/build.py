@@ -22,6 +22,7 @@ PIPELINED = [(128, 16, 4), (128, 16, 5), (128, 16, 6), (128, 8, 4), (128, 8, 6),
              (96, 16, 4), (96, 16, 5), (96, 16, 6)]
 SIMPLE = [1, 2]
 SLAB = [16, 32]            # token tiles of the short-batch kernel
+STREAM = [64, 32, 16]      # token tiles of the streamed kernel
 SIMPLE_NARROW = [32, 16]   # token tiles of the simple kernel besides 64 (one row tile per wave)
 HEADERS = [os.path.join(CSRC, "spmm_internal.h"), os.path.join(CSRC, "spmm_kernels.h"),
            os.path.join(ROOT, "include", "spmm.h")]
@@ -47,6 +48,8 @@ def units():
         out.append((f"cfg_simple{tm}_1.o", cfg, ["-DSPMM_CFG_SIMPLE=1", f"-DSPMM_CFG_SIMPLE_TM={tm}"]))
     for tm in SLAB:
         out.append((f"cfg_slab{tm}.o", cfg, [f"-DSPMM_CFG_SLAB={tm}"]))
+    for tm in STREAM:
+        out.append((f"cfg_stream{tm}.o", cfg, [f"-DSPMM_CFG_STREAM={tm}"]))
     return out
 
 

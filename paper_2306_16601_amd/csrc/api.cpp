@@ -280,7 +280,10 @@ spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t 
     if (postop == SPMM_POST_TABLE) postop = SPMM_POST_GELU;   // same kernels
     const spmm::Plan p = plan_for(h, M);
     const int post = (out_type == SPMM_OUT_S32) ? 0 : (int)postop;   // S32 output ignores the post-operator
-    if (p.slab)
+    if (p.stream)
+        std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_stream<%d, %d, %d, %d>(spmm::KernelArgs)",
+                      p.token_tile, p.waves, (int)out_type, post);
+    else if (p.slab)
         std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_slab<%d, %d, %d, %d>(spmm::KernelArgs)",
                       p.token_tile, p.waves, (int)out_type, post);
     else if (p.simple)

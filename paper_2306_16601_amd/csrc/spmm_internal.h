@@ -92,6 +92,7 @@ struct Plan {
     int waves;               // NW
     int simple;              // 1: simple kernel
     int slab;                // 1: the short-batch kernel (token tile 16 or 32, whole K resident in LDS) in its place
+    int stream;              // 1: the streamed kernel (segment staging, flat weight stream) in its place
     int max_steps;           // unroll bound of the per-segment step loop (pipelined kernel)
     int n_row_groups, n_tok_tiles, n_streams, xcd_map;
     int64_t workgroups;
@@ -99,7 +100,7 @@ struct Plan {
 
 // variant: 0 = automatic, 8 / 16 = waves per workgroup (pipelined, token tile 128 or 96),
 // 101 / 102 = simple kernel with 1 / 2 row tiles per wave (token tile 64; 101 also 32 and 16),
-// 103 = short-batch kernel (token tile 16 or 32)
+// 103 = short-batch kernel (token tile 16 or 32), 104 = streamed kernel (token tile 64, 32 or 16)
 constexpr int SLAB_SEGMENTS = 8;      // K segments the short-batch kernel keeps in LDS, token tile 16
 constexpr int SLAB_SEGMENTS_32 = 6;   // and token tile 32
 // what the plan needs to know of a packed weight

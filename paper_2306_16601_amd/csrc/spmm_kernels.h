@@ -835,4 +835,149 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
     }
 }
 
+// =======================================================================================
+// Streamed kernel (token tile 64, 32 or 16, any K): the segment-by-segment staging of the simple
+// kernel (one segment of activations in LDS, the next one prefetched into registers) with the
+// weight stream of the short-batch kernel: each wave walks all steps of its row tile in one flat
+// loop through three rotating register sets of CH steps, so a step's weights were requested two
+// sets earlier instead of when it is multiplied (the simple kernel exposes that latency at every
+// step, which is what it costs at 70-80 % sparsity).  A wave crosses into the next segment where
+// its own step list does, wherever that falls in the unrolled loop: advance() is the only place
+// with barriers, and every wave of the workgroup runs it exactly nseg - 1 times, in the loop or
+// in the drain after it (waves without a row tile, or with fewer steps, only in the drain).
+// =======================================================================================
+template <int TM, int NW, int OUT, int POST>
+__global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_stream(const KernelArgs a)
+{
+    static_assert(TM == 64 || TM == 32 || TM == 16, "token tile of the streamed kernel");
+    constexpr int STRIDE = (TM == 16) ? 16 : TM + 16, PIECES = TM / 16, CH = 8;
+    constexpr int XL = SEGMENT_ROWS * PIECES / (NW * 64);
+    static_assert(XL * NW * 64 == SEGMENT_ROWS * PIECES, "threads must tile a segment");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[SEGMENT_ROWS * STRIDE];
+
+    int tt, rg;
+    if (!decode_workgroup(a, blockIdx.x, tt, rg)) return;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const int tok0 = tt * TM;
+    const int tile = rg * NW + wave;
+    const bool have_tile = tile < a.ntiles;
+    const int n = tile * TILE_ROWS + c;
+    const int nseg = a.nseg;
+
+    // first step of every segment of this row tile, and one past the last: in LDS-free form only
+    // the current boundary is kept (a scalar), fetched when a segment is entered
+    const int32_t* const bounds = a.seg_ptr + (have_tile ? tile * nseg : 0);
+    const int s_begin = have_tile ? bounds[0] : 0;
+    const int s_end = have_tile ? bounds[nseg] : 0;
+    const int nchunks = (s_end - s_begin + CH - 1) / CH;
+
+    v4i xs[XL];
+    const bool fast = a.x_vec_ok && tok0 + TM <= a.M;
+    auto x_load = [&](const int seg) __attribute__((always_inline)) {
+        const int k0 = seg * SEGMENT_ROWS;
+        const int last = min(SEGMENT_ROWS, a.K - k0) - 1;      // rows past K repeat the last one (never multiplied)
+#pragma unroll
+        for (int u = 0; u < XL; ++u) {
+            const int p = tid + u * NW * 64;
+            const int row = k0 + min(p / PIECES, last), col = tok0 + (p % PIECES) * 16;
+            if (fast) xs[u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)col));
+            else xs[u] = load_x16(a, row, col);
+        }
+    };
+    auto x_store = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < XL; ++u) {
+            const int p = tid + u * NW * 64;
+            *(v4i*)(lds + (p / PIECES) * STRIDE + (p % PIECES) * 16) = xs[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+        }
+    };
+    x_load(0);
+
+    v4i A0[CH], A1[CH], A2[CH];
+    uint32_t I0[CH], I1[CH], I2[CH];
+    auto w_load = [&](const int chunk, v4i (&A)[CH], uint32_t (&I)[CH]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            int step = s_begin + chunk * CH + j;
+            step = (step < s_end) ? step : 0;          // step 0 is always readable
+            A[j] = *(const v4i*)(a.vals + (int64_t)step * STEP_VAL_BYTES + lane * 16);
+            I[j] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
+        }
+    };
+    w_load(0, A0, I0);
+    w_load(1, A1, I1);
+    w_load(2, A2, I2);
+
+    int init = 0;
+    if (have_tile) init = a.rowsum[n] * a.corr_mul;
+    v4i acc[PIECES];
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
+    float scale = 0.0f, bias = 0.0f;
+    if constexpr (OUT != SPMM_OUT_S32) {
+        if (have_tile && n < a.N) {
+            scale = a.w_scale[n] * a.x_scale;
+            if (a.bias) bias = a.bias[n];
+        }
+    }
+
+    x_store();
+    __syncthreads();
+    int seg = 0;                                   // the segment in LDS
+    if (nseg > 1) x_load(1);
+    int seg_end = have_tile ? bounds[1] : 0;       // first step past segment `seg` (only compared when have_tile)
+    // every wave: exactly nseg - 1 calls in total
+    auto advance = [&]() __attribute__((always_inline)) {
+        __syncthreads();                           // everyone has finished reading segment seg
+        x_store();                                 // segment seg + 1, requested when seg was entered
+        __syncthreads();
+        ++seg;
+        if (seg + 1 < nseg) x_load(seg + 1);
+        if (have_tile) seg_end = bounds[seg + 1];
+    };
+    auto multiply = [&](const int chunk, const v4i (&A)[CH], const uint32_t (&I)[CH]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            const int step = s_begin + chunk * CH + j;
+            if (step < s_end) {
+                while (step >= seg_end && seg + 1 < nseg) advance();     // (also skips empty segments)
+                const uint32_t a0 = (I[j] & 0xffffu) * STRIDE + (c & 1) * 8;
+                const uint32_t a1 = (I[j] >> 16) * STRIDE + (c & 1) * 8;
+#pragma unroll
+                for (int i = 0; i < PIECES; ++i) {
+                    const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0 + 16 * i));
+                    const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1 + 16 * i));
+                    const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
+                    acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, A[j], acc[i], 0, 0, 0);
+                }
+            }
+        }
+    };
+    for (int ch = 0; ch < nchunks; ch += 3) {
+        multiply(ch, A0, I0);
+        if (ch + 3 < nchunks) w_load(ch + 3, A0, I0);
+        if (ch + 1 < nchunks) {
+            multiply(ch + 1, A1, I1);
+            if (ch + 4 < nchunks) w_load(ch + 4, A1, I1);
+        }
+        if (ch + 2 < nchunks) {
+            multiply(ch + 2, A2, I2);
+            if (ch + 5 < nchunks) w_load(ch + 5, A2, I2);
+        }
+    }
+    while (seg + 1 < nseg) advance();              // drain: the segments after this wave's last step
+
+    if (have_tile && n < a.N) {
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) {
+            const int m0 = tok0 + 16 * i + 4 * g;
+            if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, GlobalLut{a.lut});
+        }
+    }
+}
+
 }  // namespace spmm

@@ -4,6 +4,7 @@
 //   simple kernel    : -DSPMM_CFG_SIMPLE=<1|2>      (row tiles per wave; token tile 64)
 //                      -DSPMM_CFG_SIMPLE=1 -DSPMM_CFG_SIMPLE_TM=<32|16>
 //   short-batch kernel: -DSPMM_CFG_SLAB=<16|32>      (token tile)
+//   streamed kernel  : -DSPMM_CFG_STREAM=<64|32|16>  (token tile)
 // Each defines one function launch_cfg_<...>() that picks the epilogue instantiation and
 // launches it; spmm_plan.hip calls them.
 #include "spmm_kernels.h"
@@ -42,7 +43,21 @@ static void dispatch_epilogue(spmm_out_t out_type, int postop, dim3 grid, dim3 b
 #define SPMM_CAT_(a, b) a##b
 #define SPMM_CAT(a, b) SPMM_CAT_(a, b)
 
-#if defined(SPMM_CFG_SLAB)
+#if defined(SPMM_CFG_STREAM)
+struct StreamLaunch {
+    template <int OUT, int POST>
+    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
+    {
+        hipLaunchKernelGGL((spmm_rowtile_mfma_stream<SPMM_CFG_STREAM, 8, OUT, POST>), grid, block, 0, st, a);
+    }
+};
+
+void SPMM_CAT(launch_cfg_stream, SPMM_CFG_STREAM)(spmm_out_t out_type, int postop, unsigned grid_x, unsigned grid_y,
+                                                  unsigned block, void* stream, const KernelArgs& a)
+{
+    dispatch_epilogue<StreamLaunch>(out_type, postop, dim3(grid_x, grid_y), dim3(block), (hipStream_t)stream, a);
+}
+#elif defined(SPMM_CFG_SLAB)
 struct SlabLaunch {
     template <int OUT, int POST>
     static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)

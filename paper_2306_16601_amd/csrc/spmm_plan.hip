@@ -23,14 +23,17 @@ SPMM_DECLARE_CFG(launch_cfg_simple32_1);
 SPMM_DECLARE_CFG(launch_cfg_simple16_1);
 SPMM_DECLARE_CFG(launch_cfg_slab16);
 SPMM_DECLARE_CFG(launch_cfg_slab32);
+SPMM_DECLARE_CFG(launch_cfg_stream64);
+SPMM_DECLARE_CFG(launch_cfg_stream32);
+SPMM_DECLARE_CFG(launch_cfg_stream16);
 #undef SPMM_DECLARE_CFG
 
 bool plan_supported(int token_tile, int variant)
 {
     if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16;
     if (token_tile == 96) return variant == 0 || variant == 16;
-    if (token_tile == 64) return variant == 101 || variant == 102;
-    if (token_tile == 32 || token_tile == 16) return variant == 101 || variant == 103;
+    if (token_tile == 64) return variant == 101 || variant == 102 || variant == 104;
+    if (token_tile == 32 || token_tile == 16) return variant == 101 || variant == 103 || variant == 104;
     return false;
 }
 
@@ -43,6 +46,7 @@ static void fill_pipelined(Plan& p, int64_t M, int ntiles, int num_cus, int tm, 
     p.row_tiles_per_wave = 1;
     p.simple = 0;
     p.slab = 0;
+    p.stream = 0;
     p.n_tok_tiles = (int)((M + tm - 1) / tm);
     p.n_row_groups = (ntiles + waves - 1) / waves;
     int S = num_cus / p.n_row_groups;
@@ -66,6 +70,7 @@ static void fill_simple(Plan& p, int64_t M, const WeightDims& w, int r, int tm)
     p.row_tiles_per_wave = r;
     p.simple = 1;
     p.slab = 0;
+    p.stream = 0;
     p.n_tok_tiles = (int)((M + tm - 1) / tm);
     p.n_row_groups = (ntiles + p.waves * r - 1) / (p.waves * r);
     p.n_streams = 0;
@@ -99,6 +104,11 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
         // the simple kernel
         fill_simple(p, M, w, 1, force_tm);
         p.slab = nseg <= (force_tm == 16 ? SLAB_SEGMENTS : SLAB_SEGMENTS_32);
+        return p;
+    }
+    if ((force_tm == 64 || force_tm == 32 || force_tm == 16) && variant == 104) {
+        fill_simple(p, M, w, 1, force_tm);
+        p.stream = 1;
         return p;
     }
     if (force_tm == 64 || force_tm == 32 || force_tm == 16) {
@@ -153,6 +163,11 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
             if (p.token_tile == 16 && nseg >= 5 && nseg <= SLAB_SEGMENTS) p.slab = 1;
             // (32-token tiles, 768x3072, 1024 tokens: 9.7 against 10.5 us; at 70 %: 13.1 against 13.8 us)
             if (p.token_tile == 32 && nseg >= 5 && nseg <= SLAB_SEGMENTS_32) p.slab = 1;
+            // Longest K (seven segments and more) where the slab does not fit or the tile is wider:
+            // the streamed kernel (1024x4096, 1024 tokens: 12.8 against 17.4 us at 90 %, 18.6 against
+            // 28.2 us at 70 %; 4096x4096, 384 tokens, 70 %: 20.3 against 27.2 us); with fewer segments
+            // its longer code costs more than the hidden weight latency saves.
+            if (!p.slab && nseg >= 7) p.stream = 1;
         }
     }
     if (!p.simple) {
@@ -174,7 +189,13 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop
     if (plan.simple) {
         const unsigned grid = (unsigned)plan.workgroups;
         const int key = plan.token_tile * 10 + plan.row_tiles_per_wave;
-        if (plan.slab) {
+        if (plan.stream) {
+            if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
+            if (key == 641) launch_cfg_stream64(out_type, postop, grid, 1, block, stream, a);
+            else if (key == 321) launch_cfg_stream32(out_type, postop, grid, 1, block, stream, a);
+            else if (key == 161) launch_cfg_stream16(out_type, postop, grid, 1, block, stream, a);
+            else return (int)hipErrorInvalidValue;
+        } else if (plan.slab) {
             if (a.kc != SEGMENT_ROWS) return (int)hipErrorInvalidValue;
             if (key == 161 && a.nseg <= SLAB_SEGMENTS) launch_cfg_slab16(out_type, postop, grid, 1, block, stream, a);
             else if (key == 321 && a.nseg <= SLAB_SEGMENTS_32) launch_cfg_slab32(out_type, postop, grid, 1, block, stream, a);

@@ -124,7 +124,7 @@ def test_config4_large_all_kernel_variants_agree_bitwise():
     case = wl.large_cases()[0]
     d = wl.make(case)
     a, _ = gpu_spmm(d["W"], d["X"], d, case)
-    for tuning in ((128, 0), (128, 8), (128, 16), (96, 0), (96, 16), (64, 101), (64, 102), (32, 101), (16, 101), (16, 103), (32, 103)):
+    for tuning in ((128, 0), (128, 8), (128, 16), (96, 0), (96, 16), (64, 101), (64, 102), (32, 101), (16, 101), (16, 103), (32, 103), (64, 104), (32, 104), (16, 104)):
         b, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=tuning)
         assert np.array_equal(a, b), tuning
 
@@ -221,7 +221,7 @@ def test_sum_postop(N, K, M, out_type, postop):
     assert np.mean(ref != plain) > 0.5                     # the residual matters in this test
     for ld_sum, off, tuning in ((M, 0, None), (M + 4, 0, (96, 16)), (M + 3, 1, None), (M + 8, 4, (128, 8)),
                                 (M, 0, (64, 102)), (M + 4, 0, (32, 101)), (M + 1, 3, (16, 101)), (M, 0, (16, 103)),
-                                (M + 2, 2, (16, 103)), (M + 4, 0, (32, 103))):
+                                (M + 2, 2, (16, 103)), (M + 4, 0, (32, 103)), (M, 0, (64, 104)), (M + 1, 1, (32, 104))):
         got = _run_sum(d, case, R, ld_sum, tuning, off)
         if out_type == "f32" and postop == "gelu":
             # the two sides' erfc differ by <= 1e-5 relative in GELU(y); the add then rounds once
@@ -336,8 +336,10 @@ def test_config5_whole_grid_at_full_size(NK):
     (260, 100, 257), (5, 3000, 7),
 ])
 @pytest.mark.parametrize("out_type", ["s32", "s8"])
-@pytest.mark.parametrize("tuning", [None, (128, 16), (128, 8), (96, 16), (64, 102), (32, 101), (16, 101), (16, 103), (32, 103)],
-                         ids=["default", "tile128", "tile128w8", "tile96", "simple", "simple32", "simple16", "slab", "slab32"])
+@pytest.mark.parametrize("tuning", [None, (128, 16), (128, 8), (96, 16), (64, 102), (32, 101), (16, 101), (16, 103), (32, 103),
+                                    (64, 104), (32, 104), (16, 104)],
+                         ids=["default", "tile128", "tile128w8", "tile96", "simple", "simple32", "simple16", "slab", "slab32",
+                              "stream64", "stream32", "stream16"])
 def test_ragged_shapes(N, K, M, out_type, tuning):
     case = wl.Case("ragged", N, K, M, 0.6, wl.N4K1, out_type, "none", keys=(60, N, K, M))
     check_case(case, tuning=tuning)
@@ -362,7 +364,7 @@ def test_every_epilogue_with_unaligned_leading_dims(out_type, postop):
     check_case(case)                                   # aligned, ragged tail
     check_case(case, ldx=101, ldo=93)                  # odd pitches: byte paths
     check_case(case, ldx=112, ldo=96, x_offset=3, out_offset=1)   # misaligned bases
-    for tuning in ((128, 0), (64, 101), (32, 101), (16, 101), (16, 103), (32, 103)):   # (the default here is the 16-token simple kernel)
+    for tuning in ((128, 0), (64, 101), (32, 101), (16, 101), (16, 103), (32, 103), (64, 104), (16, 104)):   # (the default here is the 16-token simple kernel)
         check_case(case, tuning=tuning)
         check_case(case, ldx=101, ldo=93, tuning=tuning)
 
@@ -386,6 +388,8 @@ def test_short_batches_long_reduction(N, K, M, s):
         assert ("mfma_slab<32" in sp.spmm_kernel_variant(h, M, "s32", "none")) == (K <= 3072)
         sp.spmm_set_tuning(h, 0, 0)             # mid-size batches: 32-token tiles, resident from five segments on
         assert ("mfma_slab<32" in sp.spmm_kernel_variant(h, 1024, "s32", "none")) == (N >= 768 and 2048 < K <= 3072)
+        if K > 4096:                            # seven segments and more without a slab: the streamed kernel
+            assert "mfma_stream<16" in sp.spmm_kernel_variant(h, M, "s32", "none")
     finally:
         sp.spmm_destroy(h)
     for ot, po in (("s32", "none"), ("f32", "gelu"), ("s8", "gelu"), ("u8", "none")):
@@ -394,6 +398,9 @@ def test_short_batches_long_reduction(N, K, M, s):
         for tm in (16, 32):                     # (32-token tiles hold K <= 3072, else the simple kernel runs)
             check_case(case, tuning=(tm, 103))
             check_case(case, tuning=(tm, 103), ldx=M + 5, ldo=M + 3)      # byte paths
+        for tm in (64, 32, 16):                 # the streamed kernel: waves cross segments at their own steps
+            check_case(case, tuning=(tm, 104))
+        check_case(case, tuning=(32, 104), ldx=M + 5, ldo=M + 3)
     check_case(wl.Case("short", N, K, M, s, wl.N1K4, "s32", "none", keys=(98, N, K, M)), tuning=(16, 103))
     check_case(wl.Case("short", N, K, M, s, wl.N1K4, "s8", "gelu", keys=(98, N, K, M)), tuning=(32, 103))
 

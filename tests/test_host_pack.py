@@ -169,6 +169,8 @@ def test_pack_argument_errors():
     assert L.spmm_set_tuning(hh, 16, 103) == sp.SPMM_OK
     assert L.spmm_set_tuning(hh, 32, 103) == sp.SPMM_OK
     assert L.spmm_set_tuning(hh, 64, 103) == sp.SPMM_E_UNSUPPORTED
+    assert L.spmm_set_tuning(hh, 64, 104) == sp.SPMM_OK
+    assert L.spmm_set_tuning(hh, 128, 104) == sp.SPMM_E_UNSUPPORTED
     assert L.spmm_set_tuning(hh, 96, 16) == sp.SPMM_OK
     assert L.spmm_set_tuning(hh, 96, 8) == sp.SPMM_E_UNSUPPORTED
     assert L.spmm_set_tuning(hh, 0, 0) == sp.SPMM_OK
@@ -261,9 +263,10 @@ def test_plan_picks_token_tile_and_waves_per_shape():
     assert kernel(768, 3072, 128) == "void spmm::spmm_rowtile_mfma_slab<16, 8, 2, 1>(spmm::KernelArgs)"
     assert kernel(1024, 4096, 32) == "void spmm::spmm_rowtile_mfma_slab<16, 8, 2, 1>(spmm::KernelArgs)"
     assert kernel(768, 2048, 128) == "void spmm::spmm_rowtile_mfma_simple<16, 8, 1, 2, 1>(spmm::KernelArgs)"
-    assert kernel(768, 4608, 128) == "void spmm::spmm_rowtile_mfma_simple<16, 8, 1, 2, 1>(spmm::KernelArgs)"
+    assert kernel(768, 4608, 128) == "void spmm::spmm_rowtile_mfma_stream<16, 8, 2, 1>(spmm::KernelArgs)"
     assert kernel(768, 768, 128, (16, 103)) == "void spmm::spmm_rowtile_mfma_slab<16, 8, 2, 1>(spmm::KernelArgs)"
     assert kernel(768, 3072, 1024) == "void spmm::spmm_rowtile_mfma_slab<32, 8, 2, 1>(spmm::KernelArgs)"
-    assert kernel(1024, 4096, 1024) == "void spmm::spmm_rowtile_mfma_simple<32, 8, 1, 2, 1>(spmm::KernelArgs)"
+    assert kernel(1024, 4096, 1024) == "void spmm::spmm_rowtile_mfma_stream<32, 8, 2, 1>(spmm::KernelArgs)"
+    assert kernel(768, 768, 128, (64, 104)) == "void spmm::spmm_rowtile_mfma_stream<64, 8, 2, 1>(spmm::KernelArgs)"
     assert kernel(768, 3072, 6144) == "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)"
     assert plan(768, 768, 128, 0.9, (128, 8)) == (128, 128, 6)
