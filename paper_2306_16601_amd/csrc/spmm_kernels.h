@@ -773,8 +773,8 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
         }
     };
     w_load(0, A0, I0);
-    w_load(1, A1, I1);
-    w_load(2, A2, I2);
+    if (nchunks > 1) w_load(1, A1, I1);
+    if (nchunks > 2) w_load(2, A2, I2);
 
 #pragma unroll
     for (int seg = 0; seg < SEGS; ++seg) {
@@ -909,8 +909,8 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_stream(const Kernel
         }
     };
     w_load(0, A0, I0);
-    w_load(1, A1, I1);
-    w_load(2, A2, I2);
+    if (nchunks > 1) w_load(1, A1, I1);
+    if (nchunks > 2) w_load(2, A2, I2);
 
     int init = 0;
     if (have_tile) init = a.rowsum[n] * a.corr_mul;
