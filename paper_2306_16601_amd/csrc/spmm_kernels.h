@@ -332,8 +332,13 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     // whenever it can, so that all row groups of one stream run on the same XCD and share its L2.
     // With xcd_map 2 the two roles are swapped (all streams of a row group on one XCD): the host's
     // choice when the packed weight is the larger operand.
-    const int stream = (a.xcd_map == 2) ? blockIdx.y : blockIdx.x, rg = (a.xcd_map == 2) ? blockIdx.x : blockIdx.y;
     const int S = a.n_streams;
+    int stream = (a.xcd_map == 2) ? blockIdx.y : blockIdx.x;
+    const int rg = (a.xcd_map == 2) ? blockIdx.x : blockIdx.y;
+    // map 1 (S is then a multiple of 8): XCD x gets the S / 8 consecutive streams from x * S / 8 on, so
+    // that token tiles next to each other in memory, which share cache lines when the tile width is
+    // not a multiple of the line, mostly run on the same XCD
+    if (a.xcd_map == 1) stream = (stream & 7) * (S >> 3) + (stream >> 3);
     const int n_my = a.tiles_per_stream + (stream < a.tiles_extra ? 1 : 0);   // token tiles of this stream (>= 1)
     const int total = n_my * a.nseg;                                          // phases
 

@@ -80,17 +80,17 @@ static void fill_simple(Plan& p, int64_t M, const WeightDims& w, int r, int tm)
                                     : (int64_t)8 * p.n_row_groups * ((p.n_tok_tiles + 7) / 8);
 }
 
-// Relative duration of a plan: the longest stream's tokens times what a token costs a workgroup
-// (plus a start-up term, in tokens), times the rounds needed when there are more workgroups
-// than CUs.  An 8-wave workgroup stages the same activations for half as many rows: measured,
-// its token tile takes about two thirds of a 16-wave one (4096x1024, 90 %: 33.0 against 25.5 us
-// for twice the tiles).
+// Relative duration of a plan: the longest stream's token tiles times what a tile costs a workgroup
+// (its tokens, plus a fixed part per tile, in tokens), plus a start-up term, times the rounds needed
+// when there are more workgroups than CUs.  An 8-wave workgroup stages the same activations for half
+// as many rows: measured, its token tile takes about two thirds of a 16-wave one (4096x1024, 90 %:
+// 33.0 against 25.5 us for twice the tiles).
 static double plan_cost(const Plan& p, int num_cus)
 {
     const int per_stream = (p.n_tok_tiles + p.n_streams - 1) / p.n_streams;
     const int64_t rounds = (p.workgroups + num_cus - 1) / num_cus;
     const double per_token = (p.waves == 16) ? 1.0 : 0.66;
-    return (double)rounds * ((double)per_stream * p.token_tile * per_token + 48.0);
+    return (double)rounds * ((double)per_stream * (p.token_tile * per_token + 16.0) + 48.0);
 }
 
 Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant)
@@ -123,16 +123,16 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
         fill_pipelined(p, M, ntiles, num_cus, force_tm ? force_tm : 128, 16);
         return p;
     } else {
-        // Token tile 128 or 96.  Measured on 6144 tokens: 96-token tiles cost more per token when
-        // the segments are short (the activation rows no longer fill cache lines, and the fixed
-        // work per tile weighs more), so they are used only from 5 steps per segment on, and
-        // there whenever they do not lengthen the longest stream.
+        // Token tile 128 or 96: 96 where it shortens the longest stream (6144 tokens and 4 row
+        // groups: 64 tiles of 96 fill the 256 CUs, 48 tiles of 128 leave a quarter idle; measured
+        // 10.6 -> 10.2 us and 27.0 -> 26.1 us at 90 %, 14.4 -> 12.4 us and 39.6 -> 33.5 us at 80 %);
+        // with 16 row groups four tiles of 96 per stream lose to three of 128 (26.7 against 25.1 us).
         fill_pipelined(p, M, ntiles, num_cus, 128, 16);
-        if (max_steps >= 5 && force_tm == 0) {
+        if (force_tm == 0) {
             Plan c{};
             c.max_steps = max_steps;
             fill_pipelined(c, M, ntiles, num_cus, 96, 16);
-            if (plan_cost(c, num_cus) <= plan_cost(p, num_cus)) p = c;
+            if (plan_cost(c, num_cus) < plan_cost(p, num_cus)) p = c;
         }
         // few row groups and few token tiles (BERT-Base shapes, short batches): 8-wave workgroups
         // are twice as many and fill more CUs

@@ -235,8 +235,8 @@ def test_plan_picks_token_tile_and_waves_per_shape():
             sp.spmm_destroy(h)
 
     assert plan(4096, 1024, 6144, 0.9) == (128, 256, 256)       # 16 row groups x 16 streams of 3 tiles
-    assert plan(1024, 1024, 6144, 0.9) == (128, 256, 192)       # short segments: 128-token tiles
-    assert plan(1024, 1024, 6144, 0.8) == (96, 256, 256)        # 5-6 steps per segment: 64 tiles of 96 fill the CUs
+    assert plan(1024, 1024, 6144, 0.9) == (96, 256, 256)        # 4 row groups: 64 tiles of 96 fill the CUs, 48 of 128 do not
+    assert plan(1024, 1024, 6144, 0.8) == (96, 256, 256)
     assert plan(768, 768, 4096, 0.9) == (128, 128, 192)         # few row groups: 8-wave workgroups
     assert plan(1024, 1024, 6144, 0.5)[1] == 128                # more than 6 steps per segment: 8 waves
     assert plan(1024, 1024, 6144, 0.9, (128, 8)) == (128, 128, 256)
@@ -268,5 +268,6 @@ def test_plan_picks_token_tile_and_waves_per_shape():
     assert kernel(768, 3072, 1024) == "void spmm::spmm_rowtile_mfma_slab<32, 8, 2, 1>(spmm::KernelArgs)"
     assert kernel(1024, 4096, 1024) == "void spmm::spmm_rowtile_mfma_stream<32, 8, 2, 1>(spmm::KernelArgs)"
     assert kernel(768, 768, 128, (64, 104)) == "void spmm::spmm_rowtile_mfma_stream<64, 8, 2, 1>(spmm::KernelArgs)"
-    assert kernel(768, 3072, 6144) == "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)"
+    assert kernel(768, 3072, 6144) == "void spmm::spmm_rowtile_mfma<96, 16, 4, 2, 1>(spmm::KernelArgs)"
+    assert kernel(4096, 1024, 6144) == "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)"
     assert plan(768, 768, 128, 0.9, (128, 8)) == (128, 128, 6)
