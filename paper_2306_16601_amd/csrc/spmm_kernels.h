@@ -555,7 +555,8 @@ __device__ __forceinline__ bool decode_workgroup(const KernelArgs& a, const int 
         tt = local % a.n_tok_tiles;
         return rg < a.n_row_groups;
     }
-    tt = xcd + 8 * (local / a.n_row_groups);
+    // (an XCD takes consecutive token tiles: tiles narrower than a cache line share their lines)
+    tt = xcd * ((a.n_tok_tiles + 7) >> 3) + local / a.n_row_groups;
     rg = local % a.n_row_groups;
     return tt < a.n_tok_tiles;
 }
