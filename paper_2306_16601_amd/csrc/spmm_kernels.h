@@ -145,8 +145,11 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
 #pragma unroll
             for (int r = 0; r < 4; ++r) q[r] = quantise<OUT, POST>(a, y[r], lut);
             uint8_t* o = (uint8_t*)a.out + (int64_t)n * a.ldo + m0;
-            if (a.out_vec_ok && valid >= 4) {
+            if (valid >= 4 && (a.out_vec_ok || ((uintptr_t)o & 3) == 0)) {
                 *(uint32_t*)o = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+            } else if (valid >= 4 && ((uintptr_t)o & 1) == 0) {
+                *(uint16_t*)o = (uint16_t)(q[0] | (q[1] << 8));
+                *(uint16_t*)(o + 2) = (uint16_t)(q[2] | (q[3] << 8));
             } else {
                 for (int r = 0; r < 4; ++r)
                     if (r < valid) o[r] = (uint8_t)q[r];
@@ -166,7 +169,23 @@ __device__ __forceinline__ v4i load_x16(const KernelArgs& a, const int krow, con
 {
     const uint8_t* src = a.X + (int64_t)krow * a.ldx + col;
     if (a.x_vec_ok && col + 16 <= a.M) return *(const v4i*)src;
-    v4i v = {0, 0, 0, 0};
+    if (col + 16 <= a.M) {
+        // any alignment (odd leading dimension or base): the aligned dwords that hold the 16
+        // bytes, shifted into place.  Every dword read holds at least one of the 16 bytes (the
+        // fifth is read only when the start is not dword-aligned), so nothing outside the pages
+        // of X is touched.
+        const uintptr_t p = (uintptr_t)src;
+        const uint32_t sh = (uint32_t)(p & 3);
+        const uint32_t* q = (const uint32_t*)(p - sh);
+        const uint32_t d0 = q[0], d1 = q[1], d2 = q[2], d3 = q[3], d4 = sh ? q[4] : 0u;
+        v4i v;
+        v[0] = (int)__builtin_amdgcn_alignbyte(d1, d0, sh);
+        v[1] = (int)__builtin_amdgcn_alignbyte(d2, d1, sh);
+        v[2] = (int)__builtin_amdgcn_alignbyte(d3, d2, sh);
+        v[3] = (int)__builtin_amdgcn_alignbyte(d4, d3, sh);
+        return v;
+    }
+    v4i v = {0, 0, 0, 0};       // the last, partial piece of a row
 #pragma unroll
     for (int j = 0; j < 16; ++j)
         if (col + j < a.M) v[j >> 2] |= (int)((uint32_t)src[j] << (8 * (j & 3)));
