@@ -165,30 +165,32 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
 __device__ __forceinline__ void wait_global_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // 16 bytes of activation row `krow` starting at token `col`; tokens >= M read as 0.
+// The general path (odd leading dimension or base, or the last, partial piece of a row) reads the
+// aligned dwords that hold the wanted bytes and shifts them into place: every dword read holds
+// at least one wanted byte, so nothing outside the pages of X is touched, and a piece costs at
+// most five loads (byte loads of 64 different rows cost a cache-line look-up each: a 13-token
+// tail made the whole launch three times longer).
 __device__ __forceinline__ v4i load_x16(const KernelArgs& a, const int krow, const int col)
 {
     const uint8_t* src = a.X + (int64_t)krow * a.ldx + col;
-    if (a.x_vec_ok && col + 16 <= a.M) return *(const v4i*)src;
-    if (col + 16 <= a.M) {
-        // any alignment (odd leading dimension or base): the aligned dwords that hold the 16
-        // bytes, shifted into place.  Every dword read holds at least one of the 16 bytes (the
-        // fifth is read only when the start is not dword-aligned), so nothing outside the pages
-        // of X is touched.
-        const uintptr_t p = (uintptr_t)src;
-        const uint32_t sh = (uint32_t)(p & 3);
-        const uint32_t* q = (const uint32_t*)(p - sh);
-        const uint32_t d0 = q[0], d1 = q[1], d2 = q[2], d3 = q[3], d4 = sh ? q[4] : 0u;
-        v4i v;
-        v[0] = (int)__builtin_amdgcn_alignbyte(d1, d0, sh);
-        v[1] = (int)__builtin_amdgcn_alignbyte(d2, d1, sh);
-        v[2] = (int)__builtin_amdgcn_alignbyte(d3, d2, sh);
-        v[3] = (int)__builtin_amdgcn_alignbyte(d4, d3, sh);
-        return v;
-    }
-    v4i v = {0, 0, 0, 0};       // the last, partial piece of a row
+    const int nbytes = min(16, a.M - col);
+    if (a.x_vec_ok && nbytes == 16) return *(const v4i*)src;
+    v4i v = {0, 0, 0, 0};
+    if (nbytes <= 0) return v;
+    const uintptr_t p = (uintptr_t)src;
+    const uint32_t sh = (uint32_t)(p & 3);
+    const uint32_t* q = (const uint32_t*)(p - sh);
+    const int span = (int)sh + nbytes;            // bytes from q[0] on that are wanted
+    uint32_t d[5];
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-        if (col + j < a.M) v[j >> 2] |= (int)((uint32_t)src[j] << (8 * (j & 3)));
+    for (int i = 0; i < 5; ++i) d[i] = (4 * i < span) ? q[i] : 0u;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t x = __builtin_amdgcn_alignbyte(d[w + 1], d[w], sh);
+        const int keep = nbytes - 4 * w;          // wanted bytes of this dword
+        const uint32_t mask = keep >= 4 ? 0xffffffffu : (keep <= 0 ? 0u : ((1u << (8 * keep)) - 1u));
+        v[w] = (int)(x & mask);
+    }
     return v;
 }
 
