@@ -54,11 +54,11 @@ void free_device(spmm_handle* h)
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-spmm::Plan plan_for(const spmm_handle* h, int64_t M)
+spmm::Plan plan_for(const spmm_handle* h, int64_t M, bool aligned = true)
 {
     const spmm::WeightDims w{h->ntiles, h->nseg, (int)h->bsr.K, h->nsteps, h->max_steps_per_segment,
                              h->max_steps_per_tile};
-    return spmm::make_plan(M, w, h->num_cus, h->force_tm, h->force_r);
+    return spmm::make_plan(M, w, h->num_cus, h->force_tm, h->force_r, aligned);
 }
 
 }  // namespace
@@ -245,7 +245,7 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
                        (h->bsr.N * ep->ld_sum * 4 < ((int64_t)1 << 31));
     }
 
-    const spmm::Plan p = plan_for(h, M);
+    const spmm::Plan p = plan_for(h, M, a.x_vec_ok && a.out_vec_ok);
     const int rc = spmm::launch_spmm(p, a, ot, (gelu ? SPMM_POST_GELU : SPMM_POST_NONE) | (ep->sum ? spmm::POST_SUM_BIT : 0),
                                      hip_stream);
     return rc == 0 ? SPMM_OK : SPMM_E_DEVICE;

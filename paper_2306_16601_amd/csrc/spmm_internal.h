@@ -110,7 +110,9 @@ struct WeightDims {
     int max_steps_per_segment, max_steps_per_tile;
 };
 bool plan_supported(int token_tile, int variant);
-Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant);
+// aligned: X and out take the 16-byte paths (base and row pitch aligned); if not, the automatic choice
+// avoids the 16-wave pipelined kernels, whose general paths are the slow bytewise ones
+Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant, bool aligned = true);
 // Launches the SpMM kernel; returns a hipError_t value as int (0 = success).
 // postop: SPMM_POST_* value, plus POST_SUM_BIT when a.sum is to be added
 constexpr int POST_SUM_BIT = 2;

@@ -104,7 +104,10 @@ __device__ __forceinline__ uint32_t quantise(const KernelArgs& a, const float y,
 
 // Generic post-operators + store for 4 consecutive tokens m0..m0+3 of output row n: any
 // alignment, any tail (the slow path of every kernel).
-template <int OUT, int POST, typename Lut>
+// WIDE: 1-byte outputs of an unaligned matrix are written in the widest pieces the address
+// allows (dword, two halves, bytes) instead of bytes; costs registers the 16-wave pipelined
+// kernels do not have (the host does not pick those for unaligned operands).
+template <int OUT, int POST, bool WIDE = false, typename Lut>
 __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, const float s, const float b,
                                         const int n, const int m0, const Lut& lut)
 {
@@ -145,9 +148,9 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
 #pragma unroll
             for (int r = 0; r < 4; ++r) q[r] = quantise<OUT, POST>(a, y[r], lut);
             uint8_t* o = (uint8_t*)a.out + (int64_t)n * a.ldo + m0;
-            if (valid >= 4 && (a.out_vec_ok || ((uintptr_t)o & 3) == 0)) {
+            if (valid >= 4 && (a.out_vec_ok || (WIDE && ((uintptr_t)o & 3) == 0))) {
                 *(uint32_t*)o = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
-            } else if (valid >= 4 && ((uintptr_t)o & 1) == 0) {
+            } else if (WIDE && valid >= 4 && ((uintptr_t)o & 1) == 0) {
                 *(uint16_t*)o = (uint16_t)(q[0] | (q[1] << 8));
                 *(uint16_t*)(o + 2) = (uint16_t)(q[2] | (q[3] << 8));
             } else {
@@ -163,6 +166,18 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
 // wait-count bookkeeping that no global load is outstanding, so the next phase's multiply
 // loop does not stall on the prefetches issued just before it.
 __device__ __forceinline__ void wait_global_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// Byte mask of a 16-byte piece of which the first nv bytes are wanted (nv <= 0: none).
+__device__ __forceinline__ v4i piece_mask(const int nv)
+{
+    v4i m;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int keep = nv - 4 * w;
+        m[w] = keep >= 4 ? -1 : (keep <= 0 ? 0 : (int)((1u << (8 * keep)) - 1u));
+    }
+    return m;
+}
 
 // 16 bytes of activation row `krow` starting at token `col`; tokens >= M read as 0.
 // The general path (odd leading dimension or base, or the last, partial piece of a row) reads the
@@ -191,6 +206,19 @@ __device__ __forceinline__ v4i load_x16(const KernelArgs& a, const int krow, con
         const uint32_t mask = keep >= 4 ? 0xffffffffu : (keep <= 0 ? 0u : ((1u << (8 * keep)) - 1u));
         v[w] = (int)(x & mask);
     }
+    return v;
+}
+
+// The same, byte by byte: few registers (the 16-wave pipelined kernels have 128 and none to
+// spare for a path they take only with unaligned activations), slow.
+__device__ __forceinline__ v4i load_x16_bytewise(const KernelArgs& a, const int krow, const int col)
+{
+    const uint8_t* src = a.X + (int64_t)krow * a.ldx + col;
+    if (a.x_vec_ok && col + 16 <= a.M) return *(const v4i*)src;
+    v4i v = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (col + j < a.M) v[j >> 2] |= (int)((uint32_t)src[j] << (8 * (j & 3)));
     return v;
 }
 
@@ -341,6 +369,10 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     constexpr int STAGERS = ROWS_PER_PASS * PIECES;
     constexpr int XLOADS = SEGMENT_ROWS / ROWS_PER_PASS;            // 16-byte loads per staging thread and phase
     static_assert(STAGERS <= NTHREADS && STAGERS % 64 == 0, "staging threads must be whole waves of the workgroup");
+    // The 16-wave kernels with 5 and 6 step slots use all 128 registers: the four mask registers of
+    // the cut piece would spill in them, so there a token count that is not a multiple of 16 takes
+    // the bytewise path for its last tile.
+    constexpr bool MASKED_TAIL = !(NW == 16 && MAXS >= 5);
     __shared__ __attribute__((aligned(16))) uint8_t lds[G::LDS];
 
     const int tid = threadIdx.x;
@@ -403,9 +435,11 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
                 const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
                 xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(x_piece * 16)));
             }
-        } else if (a.x_vec_ok && (a.M & 15) == 0) {
-            // ragged last tile of an aligned matrix whose token count is a multiple of 16: a piece
-            // is either whole or beyond the end, still branch-free
+        } else if (a.x_vec_ok && (MASKED_TAIL || (a.M & 15) == 0)) {
+            // ragged last tile of an aligned matrix: a piece is whole, beyond the end, or cut by it.
+            // The cut one is read whole as well (an aligned 16-byte chunk that holds a wanted byte
+            // lies inside the row pitch) and masked: branch-free.  (Without MASKED_TAIL only token
+            // counts that are multiples of 16 come here: no piece is cut.)
             const uint8_t* src = a.X + (int64_t)k0 * a.ldx;
             const int col = tok0 + x_piece * 16;
             const bool in = col < a.M;
@@ -413,13 +447,15 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
             for (int u = 0; u < XH; ++u) {
                 const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
                 const v4i v = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(in ? col : 0)));
-                xr[u] = in ? v : (v4i){0, 0, 0, 0};
+                if constexpr (MASKED_TAIL) xr[u] = v & piece_mask(a.M - col);
+                else xr[u] = in ? v : (v4i){0, 0, 0, 0};
             }
         } else {
 #pragma unroll
             for (int u = 0; u < XH; ++u) {
                 const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
-                xr[u] = load_x16(a, k0 + row, tok0 + x_piece * 16);
+                if constexpr (NW == 16) xr[u] = load_x16_bytewise(a, k0 + row, tok0 + x_piece * 16);
+                else xr[u] = load_x16(a, k0 + row, tok0 + x_piece * 16);
             }
         }
     };
@@ -491,7 +527,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
 #pragma unroll
                 for (int i = 0; i < PIECES; ++i) {
                     const int m0 = tok0 + 16 * i + 4 * g;
-                    if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, lut);
+                    if (m0 < a.M) finish4<OUT, POST, NW != 16>(a, acc[i], scale, bias, n, m0, lut);
                 }
             }
         }
@@ -638,8 +674,9 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
                 const int row = min(p / PIECES, last), piece = p % PIECES;
                 xs[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(piece * 16)));
             }
-        } else if (a.x_vec_ok && (a.M & 15) == 0) {
-            // ragged last tile, token count a multiple of 16: whole pieces or none, branch-free
+        } else if (a.x_vec_ok) {
+            // ragged last tile of an aligned matrix: whole pieces, none, or the cut one read whole
+            // and masked; branch-free
             const uint8_t* src = a.X + (int64_t)k0 * a.ldx;
 #pragma unroll
             for (int u = 0; u < XL; ++u) {
@@ -647,7 +684,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
                 const int row = min(p / PIECES, last), col = tok0 + (p % PIECES) * 16;
                 const bool in = col < a.M;
                 const v4i v = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(in ? col : 0)));
-                xs[u] = in ? v : (v4i){0, 0, 0, 0};
+                xs[u] = v & piece_mask(a.M - col);
             }
         } else {
 #pragma unroll
@@ -710,7 +747,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) {
             const int m0 = tok0 + 16 * i + 4 * g;
-            if (m0 < a.M) finish4<OUT, POST>(a, acc[r][i], s, bias, n, m0, lut);
+            if (m0 < a.M) finish4<OUT, POST, true>(a, acc[r][i], s, bias, n, m0, lut);
         }
     }
 }
@@ -765,8 +802,14 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
             for (int u = 0; u < PIECES; ++u) {
                 const int p = tid + u * NW * 64;
                 const int row = min(seg * SEGMENT_ROWS + p / PIECES, a.K - 1), col = tok0 + (p % PIECES) * 16;
-                if (fast) xr[seg][u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)col));
-                else xr[seg][u] = load_x16(a, row, col);
+                if (fast) {
+                    xr[seg][u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)col));
+                } else if (a.x_vec_ok) {      // ragged last tile of an aligned matrix: whole chunks, masked
+                    const v4i v = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(col < a.M ? col : 0)));
+                    xr[seg][u] = v & piece_mask(a.M - col);
+                } else {
+                    xr[seg][u] = load_x16(a, row, col);
+                }
             }
         }
     }
@@ -857,7 +900,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) {
             const int m0 = tok0 + 16 * i + 4 * g;
-            if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, GlobalLut{a.lut});
+            if (m0 < a.M) finish4<OUT, POST, true>(a, acc[i], scale, bias, n, m0, GlobalLut{a.lut});
         }
     }
 }
@@ -911,8 +954,14 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_stream(const Kernel
         for (int u = 0; u < XL; ++u) {
             const int p = tid + u * NW * 64;
             const int row = k0 + min(p / PIECES, last), col = tok0 + (p % PIECES) * 16;
-            if (fast) xs[u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)col));
-            else xs[u] = load_x16(a, row, col);
+            if (fast) {
+                xs[u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)col));
+            } else if (a.x_vec_ok) {          // ragged last tile of an aligned matrix: whole chunks, masked
+                const v4i v = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(col < a.M ? col : 0)));
+                xs[u] = v & piece_mask(a.M - col);
+            } else {
+                xs[u] = load_x16(a, row, col);
+            }
         }
     };
     auto x_store = [&]() __attribute__((always_inline)) {
@@ -1002,7 +1051,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_stream(const Kernel
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) {
             const int m0 = tok0 + 16 * i + 4 * g;
-            if (m0 < a.M) finish4<OUT, POST>(a, acc[i], scale, bias, n, m0, GlobalLut{a.lut});
+            if (m0 < a.M) finish4<OUT, POST, true>(a, acc[i], scale, bias, n, m0, GlobalLut{a.lut});
         }
     }
 }

@@ -93,7 +93,7 @@ static double plan_cost(const Plan& p, int num_cus)
     return (double)rounds * ((double)per_stream * (p.token_tile * per_token + 16.0) + 48.0);
 }
 
-Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant)
+Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant, bool aligned)
 {
     const int ntiles = w.ntiles, nseg = w.nseg, max_steps_per_segment = w.max_steps_per_segment;
     Plan p{};
@@ -117,7 +117,7 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
     }
     // 16 waves have 128 registers each: at most 6 steps per segment; denser weights run with 8
     // waves, 256 registers and half as many rows per workgroup (token tile 128 only).
-    if (max_steps > 6 || variant == 8) {
+    if (max_steps > 6 || variant == 8 || (!aligned && force_tm == 0 && variant == 0)) {
         fill_pipelined(p, M, ntiles, num_cus, 128, 8);
     } else if (force_tm == 96 || variant == 16) {
         fill_pipelined(p, M, ntiles, num_cus, force_tm ? force_tm : 128, 16);
