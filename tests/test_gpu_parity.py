@@ -356,6 +356,19 @@ def test_many_token_tiles_and_segments(N, K, M, s):
             check_case(wl.Case("multi", N, K, M, s, wl.N4K1, ot, po, keys=(66, N, K, M)), tuning=tuning)
 
 
+@pytest.mark.parametrize("N,K,M,s", [(300, 1100, 701, 0.9), (256, 600, 1299, 0.8), (272, 512, 2103, 0.7),
+                                     (1024, 1024, 1531, 0.9), (64, 3000, 517, 0.5)])
+def test_ragged_token_count_in_aligned_rows(N, K, M, s):
+    """A token count that is not a multiple of 16 in rows whose pitch is: the last tile's cut piece
+    is read whole and masked (the bytes between M and the pitch hold 0xEE and must not count), in
+    every kernel; outputs beyond M must stay untouched (the guards of gpu_spmm)."""
+    ld = (M + 15) // 16 * 16 + 16
+    for ot, po in (("s32", "none"), ("s8", "gelu"), ("f32", "none")):
+        case = wl.Case("raggedm", N, K, M, s, wl.N4K1, ot, po, keys=(68, N, K, M))
+        for tuning in (None, (128, 16), (128, 8), (96, 16), (64, 101), (32, 101), (16, 103), (32, 104)):
+            check_case(case, tuning=tuning, ldx=ld, ldo=ld)
+
+
 @pytest.mark.parametrize("out_type,postop", [("s32", "none"), ("f32", "none"), ("f32", "gelu"),
                                              ("s8", "none"), ("u8", "none"), ("s8", "gelu"), ("u8", "gelu")])
 def test_every_epilogue_with_unaligned_leading_dims(out_type, postop):
