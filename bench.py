@@ -39,10 +39,10 @@ ROTATE = 3   # distinct X/out buffer sets per SpMM (6 calls x 3 sets x ~30 MB > 
 # HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size) of the kernel
 # instantiations of the default workload, from the rocprofv3 --pmc runs summarised under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)": 46440193,
-    "void spmm::spmm_rowtile_mfma<128, 16, 6, 2, 1>(spmm::KernelArgs)": 65240039,
-    "void spmm::spmm_rowtile_mfma<96, 16, 4, 2, 1>(spmm::KernelArgs)": 31436872,
-    "void spmm::spmm_rowtile_mfma<96, 16, 6, 2, 1>(spmm::KernelArgs)": 37292315,
+    "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)": 46427316,
+    "void spmm::spmm_rowtile_mfma<128, 16, 6, 2, 1>(spmm::KernelArgs)": 65240917,
+    "void spmm::spmm_rowtile_mfma<96, 16, 4, 2, 1>(spmm::KernelArgs)": 31434285,
+    "void spmm::spmm_rowtile_mfma<96, 16, 6, 2, 1>(spmm::KernelArgs)": 37292898,
 }
 
 
