@@ -22,6 +22,15 @@
 //    workgroup decomposition: a workgroup owns a group of row tiles and walks over token
 //    tiles, so the compressed weights it needs stay in registers.
 //
+// Four kernels share the layout and the inner step (two transposing LDS reads, one matrix
+// instruction per 16 tokens); the host's plan (spmm_plan.hip) picks one by shape:
+//   spmm_rowtile_mfma         persistent, software-pipelined: long batches
+//   spmm_rowtile_mfma_simple  one workgroup per 128 rows x 16/32/64 tokens, segment by segment:
+//                             small problems, and the independent cross-check of the others
+//   spmm_rowtile_mfma_slab    the same decomposition with the whole K slab of activations in
+//                             LDS and the weights streamed: short batches, 2048 < K <= 4096
+//   spmm_rowtile_mfma_stream  segment staging with the streamed weights: short batches, longest K
+//
 // Lane roles of the matrix instruction (D = A.B, 64 lanes, g = lane / 16, c = lane % 16):
 //   A operand (activations): row = token c, bytes t = k-list slots 16g .. 16g+15
 //   B operand (weights)    : column = output row c, same k slots
