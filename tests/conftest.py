@@ -25,3 +25,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _library_is_built():
+    """The tests load the in-tree library as built; only if there is none at all is it built here
+    (hipcc cross-compiles without a GPU)."""
+    from paper_2306_16601_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2306_16601_amd import build as hip_build
+        hip_build.build(force=True)
