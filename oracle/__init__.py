@@ -32,9 +32,6 @@ def load(path: str) -> ctypes.CDLL:
     L.oracle_acc_s32.argtypes = [vp, i64, vp, i64, i64, i64, i64, i32, vp]
     L.oracle_gelu_lut.restype = ctypes.c_int
     L.oracle_gelu_lut.argtypes = [f32, f32, i32, ctypes.c_int, vp]
-    L.oracle_epilogue.restype = ctypes.c_int
-    L.oracle_epilogue.argtypes = [vp, i64, i64, vp, f32, vp, ctypes.c_int, ctypes.c_int,
-                                  f32, i32, f32, vp, vp, i64]
     L.oracle_epilogue_sum.restype = ctypes.c_int
     L.oracle_epilogue_sum.argtypes = [vp, i64, i64, vp, f32, vp, ctypes.c_int, vp, i64, ctypes.c_int,
                                       f32, i32, f32, vp, vp, i64]
@@ -118,7 +115,7 @@ def epilogue(acc: np.ndarray, w_scale: Optional[np.ndarray], x_scale: float = 1.
                                    float(np.float32(out_scale)), int(out_zero_point),
                                    float(np.float32(mid_scale)), _ptr(lut), _ptr(out), M)
     if rc != 0:
-        raise ValueError("oracle_epilogue: invalid argument combination")
+        raise ValueError("oracle_epilogue_sum: invalid argument combination")
     return out
 
 

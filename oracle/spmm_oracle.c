@@ -159,16 +159,6 @@ int oracle_epilogue_sum(const int32_t *acc, int64_t N, int64_t M,
     return 0;
 }
 
-/* The chain without Sum. */
-int oracle_epilogue(const int32_t *acc, int64_t N, int64_t M,
-                    const float *w_scale, float x_scale, const float *bias,
-                    int postop, int out_type, float out_scale, int32_t out_zp,
-                    float mid_scale, const int8_t *lut, void *out, int64_t ldo)
-{
-    return oracle_epilogue_sum(acc, N, M, w_scale, x_scale, bias, postop, NULL, 0, out_type, out_scale, out_zp,
-                               mid_scale, lut, out, ldo);
-}
-
 /* Threads an OpenMP parallel region of this library uses (reported beside timings). */
 int oracle_num_threads(void)
 {
