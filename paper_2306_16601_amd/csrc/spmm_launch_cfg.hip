@@ -43,7 +43,12 @@ static void dispatch_epilogue(spmm_out_t out_type, int postop, dim3 grid, dim3 b
 #define SPMM_CAT_(a, b) a##b
 #define SPMM_CAT(a, b) SPMM_CAT_(a, b)
 
+// The launcher structs below have the same name in every configuration's object file but launch
+// different instantiations: internal linkage keeps the linker from folding their member functions
+// into one (which would launch the wrong kernel for every configuration but the one it kept).
+
 #if defined(SPMM_CFG_STREAM)
+namespace {
 struct StreamLaunch {
     template <int OUT, int POST>
     static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
@@ -51,6 +56,7 @@ struct StreamLaunch {
         hipLaunchKernelGGL((spmm_rowtile_mfma_stream<SPMM_CFG_STREAM, 8, OUT, POST>), grid, block, 0, st, a);
     }
 };
+}  // namespace
 
 void SPMM_CAT(launch_cfg_stream, SPMM_CFG_STREAM)(spmm_out_t out_type, int postop, unsigned grid_x, unsigned grid_y,
                                                   unsigned block, void* stream, const KernelArgs& a)
@@ -58,6 +64,7 @@ void SPMM_CAT(launch_cfg_stream, SPMM_CFG_STREAM)(spmm_out_t out_type, int posto
     dispatch_epilogue<StreamLaunch>(out_type, postop, dim3(grid_x, grid_y), dim3(block), (hipStream_t)stream, a);
 }
 #elif defined(SPMM_CFG_SLAB)
+namespace {
 struct SlabLaunch {
     template <int OUT, int POST>
     static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
@@ -65,6 +72,7 @@ struct SlabLaunch {
         hipLaunchKernelGGL((spmm_rowtile_mfma_slab<SPMM_CFG_SLAB, 8, OUT, POST>), grid, block, 0, st, a);
     }
 };
+}  // namespace
 
 void SPMM_CAT(launch_cfg_slab, SPMM_CFG_SLAB)(spmm_out_t out_type, int postop, unsigned grid_x, unsigned grid_y, unsigned block, void* stream,
                      const KernelArgs& a)
@@ -79,6 +87,7 @@ void SPMM_CAT(launch_cfg_slab, SPMM_CFG_SLAB)(spmm_out_t out_type, int postop, u
 #define SPMM_SIMPLE_NAME launch_cfg_simple_
 #endif
 
+namespace {
 template <int R>
 struct SimpleLaunch {
     template <int OUT, int POST>
@@ -87,6 +96,7 @@ struct SimpleLaunch {
         hipLaunchKernelGGL((spmm_rowtile_mfma_simple<SPMM_CFG_SIMPLE_TM, 8, R, OUT, POST>), grid, block, 0, st, a);
     }
 };
+}  // namespace
 
 void SPMM_CAT(SPMM_SIMPLE_NAME, SPMM_CFG_SIMPLE)(spmm_out_t out_type, int postop, unsigned grid_x,
                                                    unsigned grid_y, unsigned block, void* stream,
@@ -96,6 +106,7 @@ void SPMM_CAT(SPMM_SIMPLE_NAME, SPMM_CFG_SIMPLE)(spmm_out_t out_type, int postop
                                                      (hipStream_t)stream, a);
 }
 #else
+namespace {
 template <int TM, int NW, int MAXS>
 struct PipeLaunch {
     template <int OUT, int POST>
@@ -104,6 +115,7 @@ struct PipeLaunch {
         hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST>), grid, block, 0, st, a);
     }
 };
+}  // namespace
 
 void SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(launch_cfg_, SPMM_CFG_TM), _), SPMM_CFG_NW), _), SPMM_CFG_MAXS)(
     spmm_out_t out_type, int postop, unsigned grid_x, unsigned grid_y, unsigned block, void* stream, const KernelArgs& a)
