@@ -147,11 +147,10 @@ spmm_status_t spmm_layout_export(const spmm_handle_t *h, uint8_t *vals_host, uin
  *   M > 0
  * Any alignment, any leading dimension >= M and any token count work.  The fast paths need X_dev
  * and out_dev (and sum) 16-byte aligned with row pitches that are multiples of 16 bytes; M itself
- * may be anything then (4096x1024 weight: 25.4 us for 6144 tokens, 27.4 us for 6143 in rows of
- * pitch 6144).  Unaligned operands are read through aligned dwords and written in the widest
- * aligned pieces: up to 1.5x slower for short batches, 4-5x for long ones (113 us for the case
- * above with pitch 6143), so pad the pitches.
- * Must be called with the handle's device current.
+ * may be anything then (a ragged last token tile costs only that tile).  Unaligned operands are
+ * read through aligned dwords and written in the widest aligned pieces, which is noticeably
+ * slower for short batches and several times slower for long ones: pad the pitches.
+ * The current HIP device must be the one the handle was packed on (SPMM_E_ARG otherwise).
  * Errors: SPMM_E_ARG (also: missing w_scale / lut, non-positive scales, zero point out
  * of range, ld_sum < M), SPMM_E_UNSUPPORTED (Sum with S32 output or with the table chain),
  * SPMM_E_DEVICE. */
@@ -167,7 +166,9 @@ spmm_status_t spmm_make_gelu_lut(float mid_scale, float out_scale, int32_t out_z
 
 /* Kernel configuration chosen for a problem (reporting / tuning aid, Section 3.2 notes
  * that the tile size is tunable offline).  Writes the token-tile width, rows per
- * workgroup and the launch grid spmm_run would use for M tokens. */
+ * workgroup and the launch grid spmm_run would use for M tokens with 16-byte aligned operands
+ * (unaligned operands may take a different kernel: their general paths need registers that the
+ * widest configurations do not have). */
 spmm_status_t spmm_plan(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
                         int32_t *token_tile, int32_t *rows_per_workgroup, int64_t *workgroups);
 
@@ -201,8 +202,9 @@ spmm_status_t spmm_set_tuning(spmm_handle_t *h, int32_t token_tile, int32_t vari
 const char *spmm_kernel_name(void);
 
 /* Full name, as a profiler prints it, of the kernel instantiation spmm_run would launch for
- * M tokens with this output type and post-operator.  buf is HOST memory of buflen bytes; the
- * name is NUL-terminated and truncated if it does not fit. */
+ * M tokens with this output type and post-operator, for 16-byte aligned operands and without
+ * the Sum operand (see spmm_plan).  buf is HOST memory of buflen bytes; the name is
+ * NUL-terminated and truncated if it does not fit. */
 spmm_status_t spmm_kernel_variant(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
                                   spmm_postop_t postop, char *buf, int64_t buflen);
 

@@ -79,7 +79,7 @@ static spmm_status_t pack_common(const int8_t* W_host, int64_t N, int64_t K, int
         spmm::bsr_from_dense(W_host, N, K, ldw, block, h->bsr);
         h->nnz_blocks = (int64_t)h->bsr.index.size();
         spmm::layout_from_bsr(h->bsr, spmm::SEGMENT_ROWS, h->hl);
-    } catch (const std::bad_alloc&) {
+    } catch (...) {   // bad_alloc, length_error, ...: nothing crosses the C boundary
         delete h;
         return SPMM_E_ALLOC;
     }
@@ -194,6 +194,10 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
 {
     if (!h || !X_dev || !ep || !out_dev) return SPMM_E_ARG;
     if (!h->on_device) return SPMM_E_ARG;   // packed with spmm_pack_host: nothing to run on
+    {   // the handle's buffers live on the device it was packed on
+        int dev_now = -1;
+        if (hipGetDevice(&dev_now) != hipSuccess || dev_now != h->device) return SPMM_E_ARG;
+    }
     if (M <= 0 || ldx < M || ldo < M) return SPMM_E_ARG;
     if (M > (int64_t)1 << 30 || ldx > (int64_t)1 << 40 || ldo > (int64_t)1 << 40) return SPMM_E_UNSUPPORTED;
     const spmm_out_t ot = ep->out_type;

@@ -115,7 +115,7 @@ bool plan_supported(int token_tile, int variant);
 Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant, bool aligned = true);
 // Launches the SpMM kernel; returns a hipError_t value as int (0 = success).
 // postop: SPMM_POST_* value, plus POST_SUM_BIT when a.sum is to be added
-constexpr int POST_SUM_BIT = 2;
+constexpr int POST_SUM_BIT = 4;   // (a bit no SPMM_POST_* value uses)
 int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop, void* stream);
 
 }  // namespace spmm

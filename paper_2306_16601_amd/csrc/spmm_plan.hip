@@ -181,6 +181,7 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
 
 int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop, void* stream)
 {
+    (void)hipGetLastError();   // an error left by an earlier, unrelated call is not this launch's
     a.n_tok_tiles = plan.n_tok_tiles;
     a.n_row_groups = plan.n_row_groups;
     a.n_streams = plan.n_streams;
