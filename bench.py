@@ -40,14 +40,25 @@ METRIC = "SpMM effective TOPS + % of HBM/int8 roofline at 70\u201390% sparsity, 
 METRIC_DETAIL = "dense-equivalent TOPS = 2NKM / time (4x1 block-sparse INT8, fused epilogue); nonzero_tops beside it"
 ROTATE = 3   # distinct X/out buffer sets per SpMM (6 calls x 3 sets x ~30 MB > 256 MB of cache)
 
-# HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size) of the kernel
-# instantiations of the default workload, from the rocprofv3 --pmc runs summarised under profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)": 46427316,
-    "void spmm::spmm_rowtile_mfma<128, 16, 6, 2, 1>(spmm::KernelArgs)": 65240917,
-    "void spmm::spmm_rowtile_mfma<96, 16, 4, 2, 1>(spmm::KernelArgs)": 31434285,
-    "void spmm::spmm_rowtile_mfma<96, 16, 6, 2, 1>(spmm::KernelArgs)": 37292898,
-}
+TRAFFIC_PROFILE = os.path.join("profiles", "spmm_rowtile_mfma_bert_large_hbm_traffic.txt")
+
+
+def measured_traffic():
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc runs, each scaled by a plain
+    copy of known size in the same run) per kernel instantiation, read from the committed summary of those
+    runs: {kernel name: bytes}, and the file they came from.  Not measured by this run."""
+    path = os.path.join(ROOT, TRAFFIC_PROFILE)
+    table = {}
+    try:
+        tail = open(path).read().split("# per kernel instantiation", 1)[1]
+    except (OSError, IndexError):
+        return table, None
+    for ln in tail.splitlines()[1:]:
+        ln = ln.strip()
+        if ln.endswith("bytes") and "(" in ln:
+            name, rest = ln.rsplit(")", 1)
+            table[name + ")"] = int(rest.split()[0])
+    return table, TRAFFIC_PROFILE
 
 
 def algorithmic_bytes(N, K, M, nnz_blocks, out_elem):
@@ -118,14 +129,60 @@ def run_grid(args, np, torch, sp, wl) -> int:
     return 0
 
 
+def time_base_f32(np, torch, sp, wl, steps, with_dense):
+    """BERT-Base layer shapes (768x768, 3072x768, 768x3072) at 90 % and 80 %, M = 32 x 128 = 4096 tokens, fp32
+    output (bias, no GELU): per call, a back-to-back loop of `steps` launches over rotating buffers, the share of
+    the HBM roofline and the ratio to the dense int8 GEMM of the same shape timed the same way."""
+    stream = torch.cuda.current_stream().cuda_stream
+    rows, dense_us = [], {}
+
+    def loop_us(fn, n):
+        for it in range(3):
+            fn(it)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for it in range(n):
+            fn(it)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    for case in wl.base_cases(batches=(32,), sparsities=(0.9, 0.8)):
+        d = wl.make(case)
+        h = sp.spmm_pack(d["W"], case.orientation)
+        N, K, nnzb, _, _ = sp.spmm_info(h)
+        ws, bias = torch.from_numpy(d["w_scale"]).cuda(), torch.from_numpy(d["bias"]).cuda()
+        ep = sp.make_epilogue(ws, d["x_scale"], 0, bias, case.postop, case.out_type, d["out_scale"], 0, d["mid_scale"])
+        Xs = [torch.from_numpy(d["X"]).cuda() for _ in range(ROTATE)]
+        outs = [torch.empty((N, case.M), dtype=torch.float32, device="cuda") for _ in range(ROTATE)]
+        runs = [sp.spmm_run_bound(h, Xs[j], case.M, case.M, ep, outs[j], case.M, stream) for j in range(ROTATE)]
+        us = loop_us(lambda it: runs[it % ROTATE](), steps)
+        key = (N, K)
+        if with_dense and key not in dense_us:
+            a = torch.randint(-128, 127, (case.M, K), dtype=torch.int8, device="cuda")
+            b = torch.randint(-128, 127, (N, K), dtype=torch.int8, device="cuda").t()
+            dense_us[key] = loop_us(lambda it: torch._int_mm(a, b), 20)
+        nbytes = algorithmic_bytes(N, K, case.M, nnzb, 4)
+        rows.append({"case": case.name, "us_back_to_back": round(us, 2), "algorithmic_bytes": int(nbytes),
+                     "roofline_frac": round(nbytes / (HBM_PEAK_GBS * 1e9) * 1e6 / us, 4),
+                     "dense_equiv_tops": round(2.0 * N * K * case.M / us / 1e6, 1),
+                     "kernel": sp.spmm_kernel_variant(h, case.M, case.out_type, case.postop),
+                     "speedup_vs_dense_gemm": round(dense_us[key] / us, 2) if key in dense_us else None})
+        sp.spmm_destroy(h)
+    return {"workload": "bert_base_layers_m4096_s90_s80_f32", "launch_mode": "eager_back_to_back", "per_call": rows}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "large_sum", "grid"],
+    ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "mini_chain", "large_sum", "grid"],
                     help="large_sum: the two BERT-Large Linears that feed a residual add (attention output and "
-                         "second feed-forward), with the Sum post-operator and fp32 output; grid: the 92-shape grid "
+                         "second feed-forward), with the Sum post-operator and fp32 output; mini_chain: the BERT-Mini "
+                         "feed-forward pair chained on the device (GELU -> uint8 code of launch 1 is the activation "
+                         "matrix of launch 2); grid: the 92-shape grid "
                          "(int8 output), geometric-mean speed-up over the dense int8 GEMM per sparsity and token count")
     ap.add_argument("--tokens", type=int, default=0,
                     help="workload base only: token count M (default 4096 = 32 sequences of 128)")
@@ -177,9 +234,13 @@ def main() -> int:
     elif args.workload == "large_sum":
         cases = [c.with_(out_type="f32", postop="none") for c in wl.large_cases() if c.N == 1024]
         wname = "bert_large_residual_linears_m6144_s90_s80_sum_f32"
+    elif args.workload == "mini_chain":
+        cases = wl.chain_cases()
+        wname = "bert_mini_ffn_pair_chained_u8_m1024_s80"
     else:
         cases = wl.mini_cases()
         wname = "bert_mini_ffn_pair_m1024_s80"
+    made = wl.make_chain(cases) if args.workload == "mini_chain" else None
     if args.only:
         cases = [c for c in cases if args.only in c.name]
         wname += "[" + args.only + "]"
@@ -191,8 +252,8 @@ def main() -> int:
 
     # ------------------------------------------------------------------ set up (not timed)
     calls = []
-    for case in cases:
-        d = wl.make(case)
+    for case_i, case in enumerate(cases):
+        d = made[case_i] if made is not None else wl.make(case)
         h = sp.spmm_pack(d["W"], case.orientation)
         if args.tuning:
             tm, r = (int(v) for v in args.tuning.split(","))
@@ -202,7 +263,8 @@ def main() -> int:
         bias = torch.from_numpy(d["bias"]).cuda() if d["bias"] is not None else None
         lut = None
         if case.postop == "gelu" and case.out_type in ("s8", "u8"):
-            lut = torch.from_numpy(sp.spmm_make_gelu_lut(d["mid_scale"], d["out_scale"], 0, case.out_type)).cuda()
+            lut = torch.from_numpy(sp.spmm_make_gelu_lut(d["mid_scale"], d["out_scale"], d["out_zero_point"],
+                                                         case.out_type)).cuda()
         Rs = None
         if args.workload == "large_sum":
             R = (wl.rng_for(97, case.N, case.M).standard_normal((case.N, case.M)) *
@@ -212,10 +274,11 @@ def main() -> int:
             eps = [sp.make_epilogue(ws, d["x_scale"], 0, bias, case.postop, case.out_type, d["out_scale"], 0,
                                     d["mid_scale"], lut, Rs[j], case.M) for j in range(ROTATE)]
         else:
-            eps = [sp.make_epilogue(ws, d["x_scale"], 0, bias, case.postop, case.out_type, d["out_scale"], 0,
-                                    d["mid_scale"], lut)] * ROTATE
+            eps = [sp.make_epilogue(ws, d["x_scale"], d["x_zero_point"], bias, case.postop, case.out_type,
+                                    d["out_scale"], d["out_zero_point"], d["mid_scale"], lut)] * ROTATE
         ep = eps[0]
-        Xs = [torch.from_numpy(d["X"]).cuda() for _ in range(ROTATE)]
+        # (chained pair: the second launch reads the first launch's output buffers)
+        Xs = calls[-1]["outs"] if d["X"] is None else [torch.from_numpy(d["X"]).cuda() for _ in range(ROTATE)]
         outs = [torch.empty((N, case.M), dtype=tdt[case.out_type], device="cuda") for _ in range(ROTATE)]
         calls.append(dict(case=case, d=d, h=h, ep=ep, eps=eps, keep=(ws, bias, lut, Rs), Xs=Xs, outs=outs, N=N, K=K,
                           M=case.M, nnzb=nnzb, padded=padded, dev_bytes=dev_bytes,
@@ -325,10 +388,13 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         b2b_us.append(e0.elapsed_time(e1) * 1e3 / args.steps)
-    if graph_ms_per_step is not None and graph_ms_per_step <= stream_ms_per_step:
-        ms_per_step, launch_mode = graph_ms_per_step, "hip_graph_replay"
-    else:
-        ms_per_step, launch_mode = stream_ms_per_step, "eager_back_to_back"
+    # `value` and the roofline use ONE launch mode: plain eager launches back to back on the stream (what a
+    # caller of spmm_run gets; graph replay of the same steps is reported beside it)
+    ms_per_step, launch_mode = stream_ms_per_step, "eager_back_to_back"
+    # Kernel durations inside the step: the events around every launch (region A) also bracket the dispatch
+    # gap between kernels, so each launch's event interval is scaled by (back-to-back step time / event-timed
+    # step time); the scaled figures are what rocprofv3's kernel trace of the same command shows.
+    gap_scale = min(1.0, stream_ms_per_step / eager_ms_per_step) if eager_ms_per_step > 0 else 1.0
 
     dense_ops = sum(c["dense_ops"] for c in calls)
     nnz_ops = sum(c["nnz_ops"] for c in calls)
@@ -419,10 +485,12 @@ def main() -> int:
             "bound": "hbm" if t_hbm >= t_int8 else "mfma", "roofline_frac": round(max(t_hbm, t_int8) / t, 4),
             "nnz_blocks": int(c["nnzb"]), "padded_blocks": int(c["padded"]),
             "plan": {"token_tile": c["plan"][0], "rows_per_wg": c["plan"][1], "workgroups": c["plan"][2]},
+            "us_in_step": round(t * gap_scale, 2), "roofline_frac_in_step": round(max(t_hbm, t_int8) / (t * gap_scale), 4),
             "us_back_to_back": round(b2b_us[ci], 2),
             "speedup_vs_dense_gemm": (round(dense[key]["us"] / b2b_us[ci], 2)
                                       if key in dense and "us" in dense[key] else None),
-            "sha256": {"W": wl.sha256(c["d"]["W"])[:16], "X": wl.sha256(c["d"]["X"])[:16]},
+            "sha256": {"W": wl.sha256(c["d"]["W"])[:16],
+                       "X": wl.sha256(c["d"]["X"])[:16] if c["d"]["X"] is not None else "output of the previous call"},
         })
     # roofline of the dominant kernel instantiation (largest share of the step): algorithmic bytes of
     # its launches / their summed durations = bytes per launch / average launch duration
@@ -431,23 +499,39 @@ def main() -> int:
         name = sp.spmm_kernel_variant(c["h"], c["M"], c["case"].out_type, c["case"].postop)
         k = by_kernel.setdefault(name, {"bytes": 0.0, "us": 0.0, "launches": 0, "nnz_ops": 0.0})
         k["bytes"] += c["bytes"]
-        k["us"] += float(avg_us[ci])
+        k["us"] += float(avg_us[ci]) * gap_scale
+        k["us_events"] = k.get("us_events", 0.0) + float(avg_us[ci])
         k["launches"] += 1
         k["nnz_ops"] += c["nnz_ops"]
     dom_name = max(by_kernel, key=lambda n: by_kernel[n]["us"])
     dom = by_kernel[dom_name]
     achieved = dom["bytes"] / (dom["us"] * 1e-6) / 1e9
+    traffic_table, traffic_file = measured_traffic()
+    # measured ceilings of the two candidate multiply instructions (registers only), beside the data-sheet peak
+    peaks = {}
+    if not args.profile:
+        try:
+            peaks = {"mfma_i32_16x16x64_i8": round(sp.spmm_measure_peak(0), 1), "dot4_i32_i8": round(sp.spmm_measure_peak(1), 1)}
+        except Exception as exc:
+            peaks = {"error": repr(exc)[:120]}
     roofline = {
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dom_name),
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_table.get(dom_name),
+        "traffic_source": (("%s (rocprofv3 --pmc summary, not measured by this run)" % traffic_file)
+                           if dom_name in traffic_table else
+                           "no entry for this kernel in %s" % (traffic_file or TRAFFIC_PROFILE)),
         "kernel": dom_name, "launches_per_step": dom["launches"],
         "avg_launch_us": round(dom["us"] / dom["launches"], 3),
         "algorithmic_bytes_per_launch": int(dom["bytes"] / dom["launches"]),
         "int8_mfma_frac": round(dom["nnz_ops"] / (dom["us"] * 1e-6) / (INT8_MFMA_PEAK_TOPS * 1e12), 4),
-        "timing": "HIP events around each eager launch (includes the dispatch gap between kernels)",
+        "avg_launch_us_between_events": round(dom["us_events"] / dom["launches"], 3),
+        "timing": "HIP events on the launch stream around every launch of the timed steps, scaled by the ratio of the "
+                  "back-to-back step time to the event-timed step time (the events also bracket the dispatch gap)",
+        "int8_mfma_measured_tops": peaks.get("mfma_i32_16x16x64_i8"), "int8_dot4_measured_tops": peaks.get("dot4_i32_i8"),
+        "int8_mfma_peak_tops": INT8_MFMA_PEAK_TOPS,
         "other_kernels": {n: {"avg_launch_us": round(v["us"] / v["launches"], 3),
                               "frac": round(v["bytes"] / (v["us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                              "traffic": MEASURED_TRAFFIC_BYTES.get(n)}
+                              "traffic": traffic_table.get(n)}
                           for n, v in by_kernel.items() if n != dom_name},
     }
 
@@ -457,21 +541,40 @@ def main() -> int:
         import oracle
         sample = [c for c in calls if abs(c["case"].sparsity - calls[0]["case"].sparsity) < 1e-9]
         ops, secs, parity = 0.0, 0.0, True
+        prev_ref = None
         for c in sample:
             d, case = c["d"], c["case"]
             launch(c, 0)
             torch.cuda.synchronize()
             got = c["outs"][0].cpu().numpy()
             t1 = time.perf_counter()
-            ref = oracle.spmm(d["W"], d["X"], d["w_scale"], d["x_scale"], d["bias"], case.postop, case.out_type,
-                              d["out_scale"], 0, d["mid_scale"], sum=d.get("R"))
+            ref = oracle.spmm(d["W"], d["X"] if d["X"] is not None else prev_ref, d["w_scale"], d["x_scale"], d["bias"],
+                              case.postop, case.out_type, d["out_scale"], d["out_zero_point"], d["mid_scale"],
+                              d["x_zero_point"], sum=d.get("R"))
+            prev_ref = ref
             secs += time.perf_counter() - t1
             ops += c["dense_ops"]
             if case.out_type == "f32" and case.postop == "gelu":
                 parity &= bool(np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref) + 1e-7))
             else:
                 parity &= bool(np.array_equal(got, ref))
+        # the same oracle on ONE thread, on the first call of the sample
+        one = None
+        try:
+            c = sample[0]
+            d, case = c["d"], c["case"]
+            nthreads = oracle.num_threads()
+            oracle.set_num_threads(1)
+            t1 = time.perf_counter()
+            oracle.spmm(d["W"], d["X"], d["w_scale"], d["x_scale"], d["bias"], case.postop, case.out_type,
+                        d["out_scale"], d["out_zero_point"], d["mid_scale"], d["x_zero_point"], sum=d.get("R"))
+            s1 = time.perf_counter() - t1
+            oracle.set_num_threads(nthreads)
+            one = {"value": round(c["dense_ops"] / s1 / 1e12, 5), "seconds": round(s1, 2), "sample": case.name}
+        except Exception as exc:
+            one = {"error": repr(exc)[:120]}
         cpu = {"value": round(ops / secs / 1e12, 5), "unit": "TOPS (dense-equivalent)", "cores": oracle.num_threads(),
+               "one_thread": one,
                "kind": "oracle", "seconds": round(secs, 2),
                "sample": "%d SpMM calls of the workload (%s), one run each" % (
                    len(sample), ", ".join(c["case"].name for c in sample)),
@@ -479,6 +582,11 @@ def main() -> int:
 
     for c in calls:
         sp.spmm_destroy(c["h"])
+
+    # the second family of shapes the target names (BERT-Base, fp32 output), beside the headline workload
+    base_f32 = None
+    if args.workload == "large" and not args.profile and not args.only and not args.tuning:
+        base_f32 = time_base_f32(np, torch, sp, wl, max(10, args.steps // 2), not args.no_dense)
 
     line = {
         "metric": METRIC, "metric_detail": METRIC_DETAIL,
@@ -489,6 +597,7 @@ def main() -> int:
                    "buffer_rotation": ROTATE},
         "nonzero_tops": round(nnz_tops, 2),
         "roofline": roofline, "cpu_baseline": cpu, "dense_int8_gemm": dense, "qkv_stacked": qkv, "per_call": rows,
+        "base_f32": base_f32,
         "ms_per_step_eager_with_events": round(eager_ms_per_step, 5),
         "ms_per_step_graph": (round(graph_ms_per_step, 5) if graph_ms_per_step is not None else None),
         "ms_per_step_eager_back_to_back": round(stream_ms_per_step, 5),

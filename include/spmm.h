@@ -208,6 +208,15 @@ const char *spmm_kernel_name(void);
 spmm_status_t spmm_kernel_variant(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
                                   spmm_postop_t postop, char *buf, int64_t buflen);
 
+/* Measured ceiling of a candidate multiply instruction on the current device, registers only
+ * (Section 3.2 builds the kernel around the widest integer multiply-accumulate the hardware has;
+ * which one that is here is decided on measured rates):
+ *   which 0: the int8 matrix instruction the kernels use (16x16x64), 1: the 4-wide int8 dot product.
+ * Runs a short kernel on the default stream, synchronises, and writes 10^12 operations per second
+ * (2 per multiply-accumulate) to *tera_ops_per_s (HOST).  Allocates a few bytes of device memory
+ * for its own use and frees them.  Errors: SPMM_E_ARG, SPMM_E_ALLOC, SPMM_E_DEVICE. */
+spmm_status_t spmm_measure_peak(int32_t which, double *tera_ops_per_s);
+
 void spmm_destroy(spmm_handle_t *h); /* NULL is allowed */
 
 const char *spmm_status_string(spmm_status_t s);

@@ -29,7 +29,7 @@ OUT_TYPES = {"s32": SPMM_OUT_S32, "f32": SPMM_OUT_F32, "s8": SPMM_OUT_S8, "u8": 
 EXPORTS = (
     "spmm_pack", "spmm_pack_host", "spmm_unpack", "spmm_info", "spmm_layout_dims",
     "spmm_layout_export", "spmm_run", "spmm_make_gelu_lut", "spmm_plan", "spmm_set_tuning",
-    "spmm_kernel_name", "spmm_kernel_variant", "spmm_destroy", "spmm_status_string",
+    "spmm_kernel_name", "spmm_kernel_variant", "spmm_measure_peak", "spmm_destroy", "spmm_status_string",
 )
 
 
@@ -93,6 +93,8 @@ def lib() -> ctypes.CDLL:
         L.spmm_kernel_name.argtypes = []
         L.spmm_kernel_variant.restype = ci
         L.spmm_kernel_variant.argtypes = [vp, i64, ci, ci, ctypes.c_char_p, i64]
+        L.spmm_measure_peak.restype = ci
+        L.spmm_measure_peak.argtypes = [i32, P(ctypes.c_double)]
         L.spmm_destroy.restype = None
         L.spmm_destroy.argtypes = [vp]
         L.spmm_status_string.restype = ctypes.c_char_p
@@ -128,6 +130,14 @@ def spmm_kernel_variant(handle: int, M: int, out_type="s32", postop="none") -> s
     buf = ctypes.create_string_buffer(256)
     _check(lib().spmm_kernel_variant(handle, int(M), ot, po, buf, 256), "spmm_kernel_variant")
     return buf.value.decode()
+
+
+def spmm_measure_peak(which: int) -> float:
+    """Measured rate (10^12 operations per second) of the int8 matrix instruction (0) or of the
+    4-wide int8 dot product (1) on the current device."""
+    v = ctypes.c_double()
+    _check(lib().spmm_measure_peak(int(which), ctypes.byref(v)), "spmm_measure_peak")
+    return float(v.value)
 
 
 def _pack(fn, W: np.ndarray, block) -> int:

@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspmm4x1.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-HOST_SOURCES = ["api.cpp", "pack.cpp", "spmm_plan.hip"]
+HOST_SOURCES = ["api.cpp", "pack.cpp", "spmm_plan.hip", "spmm_peak.hip"]
 # (token tile, waves, step slots) of the pipelined kernel; row tiles per wave of the simple kernel
 PIPELINED = [(128, 16, 4), (128, 16, 5), (128, 16, 6), (128, 8, 4), (128, 8, 6), (128, 8, 8),
              (96, 16, 4), (96, 16, 5), (96, 16, 6)]

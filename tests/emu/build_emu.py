@@ -63,6 +63,8 @@ def build(force: bool = False) -> str:
              "-I", os.path.join(HERE, "include"), "-I", os.path.join(ROOT, "include"), "-I", src, "-x", "c++"]
     cmds, objs = [], []
     for name, path, defs in B.units():
+        if os.path.basename(path) == "spmm_peak.hip":
+            continue          # instruction-rate measurement: nothing to emulate (stubbed in emu.cpp)
         o = os.path.join(obj, name)
         objs.append(o)
         cmds.append([CXX, *flags, *defs, "-c", os.path.join(src, os.path.basename(path)), "-o", o])

@@ -317,5 +317,7 @@ struct Install { Install() {
     stack_t ss{}; ss.ss_sp = altstack; ss.ss_size = sizeof(altstack); sigaltstack(&ss, nullptr);
     struct sigaction sa{}; sa.sa_sigaction = on_segv; sa.sa_flags = SA_SIGINFO | SA_ONSTACK; sigaction(SIGSEGV, &sa, nullptr); } } install;
 }
+// the instruction-rate measurement has no meaning on the host
+extern "C" int spmm_measure_peak(int, double*) { return 2; /* SPMM_E_UNSUPPORTED */ }
 extern "C" void* emu_alloc(size_t bytes) { return emu::dev_alloc(bytes); }
 extern "C" void emu_free(void* p) { emu::dev_free(p); }

@@ -165,6 +165,40 @@ def test_table_of_any_elementwise_chain(out_type):
         assert len(np.unique(got)) > 8      # the table is really exercised
 
 
+def test_chained_ffn_pair_stays_quantised_on_device():
+    # Figure 3 / Algorithm 2: W1 -> bias -> GELU -> uint8 (table chain, with a zero point) feeds W2 -> int8
+    # directly: the first launch's output buffer is the second launch's activation matrix, no fp32 tensor
+    # and no host round trip between them.  Both stages against the oracle chained the same way.
+    cases = wl.chain_cases()
+    d1, d2 = wl.make_chain(cases)
+    c1, c2 = cases
+    h1, h2 = sp.spmm_pack(d1["W"], c1.orientation), sp.spmm_pack(d2["W"], c2.orientation)
+    try:
+        M = c1.M
+        X = dev(d1["X"])
+        hid = torch.full((c1.N, M), 0xA5, dtype=torch.uint8, device="cuda")
+        out = torch.full((c2.N, M), 0x5A, dtype=torch.int8, device="cuda")
+        lut = dev(sp.spmm_make_gelu_lut(d1["mid_scale"], d1["out_scale"], d1["out_zero_point"], "u8"))
+        ep1 = sp.make_epilogue(dev(d1["w_scale"]), d1["x_scale"], 0, dev(d1["bias"]), "gelu", "u8",
+                               d1["out_scale"], d1["out_zero_point"], d1["mid_scale"], lut)
+        ep2 = sp.make_epilogue(dev(d2["w_scale"]), d2["x_scale"], d2["x_zero_point"], dev(d2["bias"]), "none", "s8",
+                               d2["out_scale"], 0)
+        st = torch.cuda.current_stream().cuda_stream
+        sp.spmm_run(h1, X, M, M, ep1, hid, M, st)
+        sp.spmm_run(h2, hid, M, M, ep2, out, M, st)       # same stream: ordered behind the first
+        torch.cuda.synchronize()
+        ref1 = oracle.spmm(d1["W"], d1["X"], d1["w_scale"], d1["x_scale"], d1["bias"], "gelu", "u8",
+                           d1["out_scale"], d1["out_zero_point"], d1["mid_scale"])
+        ref2 = oracle.spmm(d2["W"], ref1, d2["w_scale"], d2["x_scale"], d2["bias"], "none", "s8",
+                           d2["out_scale"], 0, 1.0, d2["x_zero_point"])
+        assert d1["out_zero_point"] > 0 and len(np.unique(ref1)) > 100 and len(np.unique(ref2)) > 100
+        assert np.array_equal(hid.cpu().numpy(), ref1)
+        assert np.array_equal(out.cpu().numpy(), ref2)
+    finally:
+        sp.spmm_destroy(h1)
+        sp.spmm_destroy(h2)
+
+
 def test_stacked_qkv_is_three_projections():
     # Q, K and V share one X (Figure 3(a)): packing the three weights as one [3N, K] matrix gives
     # one launch whose output is the three separate outputs stacked, bit for bit.

@@ -85,3 +85,11 @@ def test_quant_scales_clip_a_small_fraction():
     q = oracle.spmm(d["W"], d["X"], d["w_scale"], d["x_scale"], d["bias"], "none", "s8", d["out_scale"])
     sat = float(((q == 127) | (q == -128)).mean())
     assert 0.0 < sat < 0.02
+
+
+def test_chain_pair_inputs_link_the_two_stages():
+    cases = wl.chain_cases()
+    d1, d2 = wl.make_chain(cases)
+    assert cases[0].N == cases[1].K and cases[0].M == cases[1].M
+    assert d2["X"] is None and d2["x_scale"] == d1["out_scale"] and d2["x_zero_point"] == d1["out_zero_point"]
+    assert 0 < d1["out_zero_point"] < 64 and d1["out_scale"] > 0 and d2["out_scale"] > 0

@@ -218,6 +218,40 @@ def mini_cases(orientation: str = N4K1) -> List[Case]:
     ]
 
 
+def chain_cases(orientation: str = N4K1) -> List[Case]:
+    """Config 2 as a chained pair (Figure 3 / Algorithm 2: a quantised operator feeding the next one with
+    no fp32 tensor between them): W1 bias + GELU -> uint8 code with a zero point (the table chain), whose
+    output IS the activation matrix of W2 -> int8.  Inputs of the pair come from make_chain()."""
+    M = 8 * 128
+    return [
+        Case("chain_ffn1_1024x256_m1024_s80", 1024, 256, M, 0.80, orientation, OUT_U8,
+             POST_GELU, keys=(2, 1024, 256, M, 80)),
+        Case("chain_ffn2_256x1024_m1024_s80", 256, 1024, M, 0.80, orientation, OUT_S8,
+             POST_NONE, keys=(2, 256, 1024, M, 80)),
+    ]
+
+
+def make_chain(cases: List[Case]) -> List[Dict[str, object]]:
+    """Inputs of chain_cases(): the first stage's uint8 output scale / zero point (GELU output lies in
+    [-0.17, ~4 sigma]: the code covers that range) are the second stage's activation scale / zero
+    point; the second stage has no X of its own (d["X"] is None)."""
+    c1, c2 = cases
+    d1, d2 = make(c1), make(c2)
+    sigma1 = preact_sigma(c1.K, c1.sparsity)
+    h_scale = float(np.float32((4.0 * sigma1 + 0.17) / 255.0))
+    h_zp = int(round_half_up(0.17 / h_scale))
+    d1["out_scale"], d1["out_zero_point"] = h_scale, h_zp
+    # second stage: E[(h - zp)^2 h_scale^2] ~ E[GELU(y)^2] ~ sigma1^2 / 2 for y ~ N(0, sigma1^2)
+    nnz_row = (1.0 - c2.sparsity) * c2.K
+    e_w2 = 128.0 * 255.0 / 6.0
+    e_s2 = (1e-6 + 1e-5 + 1e-4) / 3.0
+    sigma2 = math.sqrt(nnz_row * e_w2 * (sigma1 ** 2 / 2.0) * e_s2 + 1.0)
+    d2["X"] = None
+    d2["x_scale"], d2["x_zero_point"] = h_scale, h_zp
+    d2["out_scale"] = float(np.float32(4.0 * sigma2 / 127.0))
+    return [d1, d2]
+
+
 def base_cases(orientation: str = N4K1, batches=(1, 8, 32), sparsities=SPARSITIES) -> List[Case]:
     """Config 3: BERT-Base layer shapes x sparsity sweep x M = 128*batch, fp32 output."""
     out = []
