@@ -92,9 +92,14 @@ def run_grid(args, np, torch, sp, wl) -> int:
 
     dense_us, rows = {}, []
     ops = t_sparse = 0.0
+    nnz_total = padded_total = 0
     for case in cases:
         d = wl.make(case)
-        h = sp.spmm_pack(d["W"], case.orientation)
+        # (timing only: the row order of scale and bias does not matter here)
+        h = sp.spmm_pack_ex(d["W"], case.orientation, reorder_rows=True) if args.reorder else sp.spmm_pack(d["W"], case.orientation)
+        info = sp.spmm_info(h)
+        nnz_total += info[2]
+        padded_total += info[3]
         ws, bias, X = (torch.from_numpy(d[k]).cuda() for k in ("w_scale", "bias", "X"))
         out = torch.empty((case.N, case.M), dtype=torch.int8, device="cuda")
         ep = sp.make_epilogue(ws, d["x_scale"], 0, bias, "none", "s8", d["out_scale"], 0)
@@ -121,7 +126,9 @@ def run_grid(args, np, torch, sp, wl) -> int:
         "value": round(ops / t_sparse / 1e6, 2), "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": 3,
         "ms_per_step": round(t_sparse / 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "shape_grid_%d_cases_s8" % len(rows), "launch_mode": "eager_back_to_back"},
+        "config": {"workload": "shape_grid_%d_cases_s8" % len(rows) + ("[rows reordered]" if args.reorder else ""),
+                   "launch_mode": "eager_back_to_back"},
+        "padded_over_nnz_blocks": round(padded_total / max(1, nnz_total), 3),
         "speedup_vs_dense_gemm": table,
         "slowest_vs_dense": [{"case": c.name, "us": round(us, 2), "dense_us": round(dn, 2)}
                              for c, us, dn in sorted([r for r in rows if r[2]], key=lambda r: r[2] / r[1])[:5]],
@@ -178,7 +185,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "mini_chain", "large_sum", "grid"],
+    ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "mini_chain", "large_sum", "grid", "clustered"],
                     help="large_sum: the two BERT-Large Linears that feed a residual add (attention output and "
                          "second feed-forward), with the Sum post-operator and fp32 output; mini_chain: the BERT-Mini "
                          "feed-forward pair chained on the device (GELU -> uint8 code of launch 1 is the activation "
@@ -187,6 +194,9 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=0,
                     help="workload base only: token count M (default 4096 = 32 sequences of 128)")
     ap.add_argument("--sparsities", default="", help="workload base only: comma list, e.g. 0.7,0.8,0.9")
+    ap.add_argument("--reorder", action="store_true",
+                    help="pack with SPMM_PACK_REORDER_ROWS (rows clustered by k overlap); outputs and per-row "
+                         "operands are then in the library's row order")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--tuning", default="", help="token_tile,variant override passed to spmm_set_tuning")
@@ -237,10 +247,15 @@ def main() -> int:
     elif args.workload == "mini_chain":
         cases = wl.chain_cases()
         wname = "bert_mini_ffn_pair_chained_u8_m1024_s80"
+    elif args.workload == "clustered":
+        cases = wl.clustered_cases()
+        wname = "clustered32_4096x1024_m6144_s90_s80_gelu_s8"
     else:
         cases = wl.mini_cases()
         wname = "bert_mini_ffn_pair_m1024_s80"
     made = wl.make_chain(cases) if args.workload == "mini_chain" else None
+    if args.reorder:
+        wname += "[rows reordered]"
     if args.only:
         cases = [c for c in cases if args.only in c.name]
         wname += "[" + args.only + "]"
@@ -254,7 +269,19 @@ def main() -> int:
     calls = []
     for case_i, case in enumerate(cases):
         d = made[case_i] if made is not None else wl.make(case)
-        h = sp.spmm_pack(d["W"], case.orientation)
+        if args.reorder:
+            if made is not None:
+                print("bench.py: --reorder is not available for the chained pair", file=sys.stderr)
+                return 2
+            h = sp.spmm_pack_ex(d["W"], case.orientation, reorder_rows=True)
+            # from here on the problem is the one the handle stands for: rows in the library's order
+            order = sp.spmm_row_order(h)
+            d["W"] = np.ascontiguousarray(d["W"][order])
+            d["w_scale"] = np.ascontiguousarray(d["w_scale"][order])
+            if d["bias"] is not None:
+                d["bias"] = np.ascontiguousarray(d["bias"][order])
+        else:
+            h = sp.spmm_pack(d["W"], case.orientation)
         if args.tuning:
             tm, r = (int(v) for v in args.tuning.split(","))
             sp.spmm_set_tuning(h, tm, r)

@@ -107,8 +107,30 @@ spmm_status_t spmm_pack(const int8_t *W_host, int64_t N, int64_t K, int64_t ldw,
 spmm_status_t spmm_pack_host(const int8_t *W_host, int64_t N, int64_t K, int64_t ldw,
                              spmm_block_t block, spmm_handle_t **out_handle);
 
-/* Exact inverse of spmm_pack: writes the dense-with-zeros matrix into host memory
- * W_host_out [N][ldw], ldw >= K (all N*K entries are written). */
+/* spmm_pack with options (Section 3.2: the blocking is tunable offline for a given weight).
+ *   flags   SPMM_PACK_HOST_ONLY     as spmm_pack_host
+ *           SPMM_PACK_REORDER_ROWS  the library chooses the ORDER of the output rows: whole
+ *                   block-rows (4 consecutive rows for N4K1, single rows for N1K4; a trailing
+ *                   partial block-row stays last) are clustered by the overlap of their k
+ *                   lists, so that a row tile multiplies a smaller union.  The handle then
+ *                   stands for the weight with its rows in that order: row i of the output,
+ *                   of w_scale, of bias and of the Sum operand in spmm_run is row
+ *                   order[i] of the matrix given here (spmm_row_order).  A following layer
+ *                   absorbs the order by the same permutation of its weight's columns, done
+ *                   once offline.  spmm_unpack still returns the matrix as given.
+ *   other bits: SPMM_E_ARG. */
+#define SPMM_PACK_HOST_ONLY 1u
+#define SPMM_PACK_REORDER_ROWS 2u
+spmm_status_t spmm_pack_ex(const int8_t *W_host, int64_t N, int64_t K, int64_t ldw,
+                           spmm_block_t block, uint32_t flags, spmm_handle_t **out_handle);
+
+/* The row order of a packed weight: order_host (host, int32 [N]) receives, for every row i
+ * the handle computes, the row of the caller's matrix it is (the identity unless the weight
+ * was packed with SPMM_PACK_REORDER_ROWS; always a permutation of 0..N-1). */
+spmm_status_t spmm_row_order(const spmm_handle_t *h, int32_t *order_host);
+
+/* Exact inverse of spmm_pack (whatever the row order chosen): writes the dense-with-zeros
+ * matrix into host memory W_host_out [N][ldw], ldw >= K (all N*K entries are written). */
 spmm_status_t spmm_unpack(const spmm_handle_t *h, int8_t *W_host_out, int64_t ldw);
 
 /* Sizes of a packed weight.  Any output pointer may be NULL.

@@ -27,7 +27,7 @@ POSTOPS = {"none": SPMM_POST_NONE, "gelu": SPMM_POST_GELU, "table": SPMM_POST_TA
 OUT_TYPES = {"s32": SPMM_OUT_S32, "f32": SPMM_OUT_F32, "s8": SPMM_OUT_S8, "u8": SPMM_OUT_U8}
 
 EXPORTS = (
-    "spmm_pack", "spmm_pack_host", "spmm_unpack", "spmm_info", "spmm_layout_dims",
+    "spmm_pack", "spmm_pack_host", "spmm_pack_ex", "spmm_row_order", "spmm_unpack", "spmm_info", "spmm_layout_dims",
     "spmm_layout_export", "spmm_run", "spmm_make_gelu_lut", "spmm_plan", "spmm_set_tuning",
     "spmm_kernel_name", "spmm_kernel_variant", "spmm_measure_peak", "spmm_destroy", "spmm_status_string",
 )
@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.spmm_pack.argtypes = [vp, i64, i64, i64, ci, P(vp)]
         L.spmm_pack_host.restype = ci
         L.spmm_pack_host.argtypes = [vp, i64, i64, i64, ci, P(vp)]
+        L.spmm_pack_ex.restype = ci
+        L.spmm_pack_ex.argtypes = [vp, i64, i64, i64, ci, ctypes.c_uint32, P(vp)]
+        L.spmm_row_order.restype = ci
+        L.spmm_row_order.argtypes = [vp, vp]
         L.spmm_unpack.restype = ci
         L.spmm_unpack.argtypes = [vp, vp, i64]
         L.spmm_info.restype = ci
@@ -157,6 +161,29 @@ def spmm_pack(W: np.ndarray, block="n4k1") -> int:
 def spmm_pack_host(W: np.ndarray, block="n4k1") -> int:
     """Host-only compression (no GPU needed); the handle cannot be run."""
     return _pack(lib().spmm_pack_host, W, block)
+
+
+SPMM_PACK_HOST_ONLY, SPMM_PACK_REORDER_ROWS = 1, 2
+
+
+def spmm_pack_ex(W: np.ndarray, block="n4k1", host_only=False, reorder_rows=False) -> int:
+    """spmm_pack with options; with reorder_rows the handle stands for W[spmm_row_order(handle)]."""
+    assert isinstance(W, np.ndarray) and W.dtype == np.int8 and W.ndim == 2 and W.strides[1] == 1
+    N, K = W.shape
+    h = ctypes.c_void_p()
+    b = BLOCKS[block] if isinstance(block, str) else int(block)
+    flags = (SPMM_PACK_HOST_ONLY if host_only else 0) | (SPMM_PACK_REORDER_ROWS if reorder_rows else 0)
+    _check(lib().spmm_pack_ex(W.ctypes.data_as(ctypes.c_void_p), N, K, W.strides[0], b, flags, ctypes.byref(h)),
+           "spmm_pack_ex")
+    return h.value
+
+
+def spmm_row_order(handle: int) -> np.ndarray:
+    """order[i] = row of the packed matrix that row i of the handle's outputs and per-row operands is."""
+    N = spmm_info(handle)[0]
+    order = np.empty(N, dtype=np.int32)
+    _check(lib().spmm_row_order(handle, order.ctypes.data_as(ctypes.c_void_p)), "spmm_row_order")
+    return order
 
 
 def spmm_unpack(handle: int) -> np.ndarray:

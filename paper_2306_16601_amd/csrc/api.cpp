@@ -10,7 +10,8 @@
 #include "spmm_internal.h"
 
 struct spmm_handle {
-    spmm::Bsr bsr;                 // canonical host copy (unpack / info)
+    spmm::Bsr bsr;                 // canonical host copy (unpack / info), rows in the caller's order
+    std::vector<int32_t> row_order;   // empty: identity; else row i of the packed weight = row row_order[i]
     int64_t nnz_blocks = 0;
     int device = 0;
     spmm::HostLayout hl;           // host copy of the row-tile union layout
@@ -66,7 +67,7 @@ spmm::Plan plan_for(const spmm_handle* h, int64_t M, bool aligned = true)
 extern "C" {
 
 static spmm_status_t pack_common(const int8_t* W_host, int64_t N, int64_t K, int64_t ldw, spmm_block_t block,
-                                 bool to_device, spmm_handle_t** out_handle)
+                                 bool to_device, bool reorder, spmm_handle_t** out_handle)
 {
     if (!W_host || !out_handle) return SPMM_E_ARG;
     if (N <= 0 || K <= 0 || ldw < K) return SPMM_E_ARG;
@@ -78,7 +79,14 @@ static spmm_status_t pack_common(const int8_t* W_host, int64_t N, int64_t K, int
         h = new spmm_handle();
         spmm::bsr_from_dense(W_host, N, K, ldw, block, h->bsr);
         h->nnz_blocks = (int64_t)h->bsr.index.size();
-        spmm::layout_from_bsr(h->bsr, spmm::SEGMENT_ROWS, h->hl);
+        if (reorder) {
+            spmm::order_rows_by_k_overlap(h->bsr, spmm::SEGMENT_ROWS, h->row_order);
+            spmm::Bsr ordered;
+            spmm::bsr_permute_rows(h->bsr, h->row_order, ordered);
+            spmm::layout_from_bsr(ordered, spmm::SEGMENT_ROWS, h->hl);
+        } else {
+            spmm::layout_from_bsr(h->bsr, spmm::SEGMENT_ROWS, h->hl);
+        }
     } catch (...) {   // bad_alloc, length_error, ...: nothing crosses the C boundary
         delete h;
         return SPMM_E_ALLOC;
@@ -113,13 +121,28 @@ static spmm_status_t pack_common(const int8_t* W_host, int64_t N, int64_t K, int
 spmm_status_t spmm_pack(const int8_t* W_host, int64_t N, int64_t K, int64_t ldw, spmm_block_t block,
                         spmm_handle_t** out_handle)
 {
-    return pack_common(W_host, N, K, ldw, block, true, out_handle);
+    return pack_common(W_host, N, K, ldw, block, true, false, out_handle);
 }
 
 spmm_status_t spmm_pack_host(const int8_t* W_host, int64_t N, int64_t K, int64_t ldw, spmm_block_t block,
                              spmm_handle_t** out_handle)
 {
-    return pack_common(W_host, N, K, ldw, block, false, out_handle);
+    return pack_common(W_host, N, K, ldw, block, false, false, out_handle);
+}
+
+spmm_status_t spmm_pack_ex(const int8_t* W_host, int64_t N, int64_t K, int64_t ldw, spmm_block_t block,
+                           uint32_t flags, spmm_handle_t** out_handle)
+{
+    if (flags & ~(uint32_t)(SPMM_PACK_HOST_ONLY | SPMM_PACK_REORDER_ROWS)) return SPMM_E_ARG;
+    return pack_common(W_host, N, K, ldw, block, (flags & SPMM_PACK_HOST_ONLY) == 0,
+                       (flags & SPMM_PACK_REORDER_ROWS) != 0, out_handle);
+}
+
+spmm_status_t spmm_row_order(const spmm_handle_t* h, int32_t* order_host)
+{
+    if (!h || !order_host) return SPMM_E_ARG;
+    for (int64_t i = 0; i < h->bsr.N; ++i) order_host[i] = h->row_order.empty() ? (int32_t)i : h->row_order[(size_t)i];
+    return SPMM_OK;
 }
 
 spmm_status_t spmm_layout_dims(const spmm_handle_t* h, int32_t* tile_rows, int32_t* step_k,

@@ -181,6 +181,127 @@ static void arrange_for_lds_banks(const std::vector<int32_t>& list, int rows_in_
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Offline ordering of the output rows (Section 3.2: what can be tuned offline for a given
+// sparse weight).  A row tile multiplies the UNION of the k lists of its rows, padded to
+// whole steps, so rows with similar lists belong in one tile.  The movable unit is what
+// keeps the block structure: a 4x1 block-row (four consecutive rows) in the paper's
+// orientation, a single row for 1x4 blocks; a trailing partial block-row stays last, so the
+// first N rows of the new order are exactly the N rows of the weight.
+//
+// Greedy clustering: units are taken heaviest first; a tile is opened with the heaviest
+// unit left and filled with the units (among the next `window` in that order) that add the
+// fewest steps, then the fewest listed k, to the tile's per-segment unions.  Heaviest-first
+// also puts rows of similar length next to each other, which is what the waves of one
+// workgroup (one row tile each, in lock-step per segment) want.
+// ---------------------------------------------------------------------------------------
+namespace {
+
+struct KSet {
+    std::vector<uint64_t> w;   // one bit per k
+};
+
+inline int popcount64(uint64_t x) { return __builtin_popcountll(x); }
+
+// steps of a union, per segment of kc (a multiple of 64) positions
+int64_t steps_of(const std::vector<uint64_t>& u, int words_per_seg, int64_t* listed)
+{
+    int64_t steps = 0, total = 0;
+    for (size_t w0 = 0; w0 < u.size(); w0 += (size_t)words_per_seg) {
+        int cnt = 0;
+        for (size_t w = w0; w < std::min(u.size(), w0 + (size_t)words_per_seg); ++w) cnt += popcount64(u[w]);
+        steps += (cnt + STEP_K - 1) / STEP_K;
+        total += cnt;
+    }
+    if (listed) *listed = total;
+    return steps;
+}
+
+}  // namespace
+
+void order_rows_by_k_overlap(const Bsr& b, int kc, std::vector<int32_t>& row_order)
+{
+    const bool n4 = (b.block == SPMM_BLOCK_N4K1);
+    const int unit_rows = n4 ? 4 : 1;
+    const int group = TILE_ROWS / unit_rows;             // units per row tile
+    const int64_t full_units = n4 ? b.N / 4 : b.N;       // a trailing partial block-row is not moved
+    const int words = (int)((b.K + 63) / 64), words_per_seg = kc / 64;
+
+    std::vector<KSet> ks((size_t)full_units);
+    std::vector<int64_t> weight((size_t)full_units);
+    for (int64_t u = 0; u < full_units; ++u) {
+        ks[(size_t)u].w.assign((size_t)words, 0);
+        weight[(size_t)u] = b.row_ptr[u + 1] - b.row_ptr[u];
+        for (int64_t e = b.row_ptr[u]; e < b.row_ptr[u + 1]; ++e) {
+            if (n4) {
+                const int64_t k = b.index[e];
+                ks[(size_t)u].w[(size_t)(k >> 6)] |= (uint64_t)1 << (k & 63);
+            } else {
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t k = (int64_t)b.index[e] * 4 + j;
+                    if (k < b.K) ks[(size_t)u].w[(size_t)(k >> 6)] |= (uint64_t)1 << (k & 63);
+                }
+            }
+        }
+    }
+    std::vector<int64_t> by_weight((size_t)full_units);
+    for (int64_t u = 0; u < full_units; ++u) by_weight[(size_t)u] = u;
+    std::stable_sort(by_weight.begin(), by_weight.end(),
+                     [&](int64_t x, int64_t y) { return weight[(size_t)x] > weight[(size_t)y]; });
+
+    const int64_t window = 512;
+    std::vector<char> used((size_t)full_units, 0);
+    std::vector<int64_t> unit_order;
+    unit_order.reserve((size_t)full_units);
+    std::vector<uint64_t> uni((size_t)words), trial((size_t)words);
+    int64_t first_free = 0;   // position in by_weight of the heaviest unit not yet placed
+    while ((int64_t)unit_order.size() < full_units) {
+        while (used[(size_t)by_weight[(size_t)first_free]]) ++first_free;
+        const int64_t seed = by_weight[(size_t)first_free];
+        used[(size_t)seed] = 1;
+        unit_order.push_back(seed);
+        uni = ks[(size_t)seed].w;
+        for (int slot = 1; slot < group && (int64_t)unit_order.size() < full_units; ++slot) {
+            int64_t best = -1, best_steps = 0, best_listed = 0, seen = 0;
+            for (int64_t p = first_free; p < full_units && seen < window; ++p) {
+                const int64_t u = by_weight[(size_t)p];
+                if (used[(size_t)u]) continue;
+                ++seen;
+                for (int w = 0; w < words; ++w) trial[(size_t)w] = uni[(size_t)w] | ks[(size_t)u].w[(size_t)w];
+                int64_t listed = 0;
+                const int64_t st = steps_of(trial, words_per_seg, &listed);
+                if (best < 0 || st < best_steps || (st == best_steps && listed < best_listed)) {
+                    best = u; best_steps = st; best_listed = listed;
+                }
+            }
+            used[(size_t)best] = 1;
+            unit_order.push_back(best);
+            for (int w = 0; w < words; ++w) uni[(size_t)w] |= ks[(size_t)best].w[(size_t)w];
+        }
+    }
+    row_order.clear();
+    row_order.reserve((size_t)b.N);
+    for (const int64_t u : unit_order)
+        for (int i = 0; i < unit_rows; ++i) row_order.push_back((int32_t)(u * unit_rows + i));
+    for (int64_t n = full_units * unit_rows; n < b.N; ++n) row_order.push_back((int32_t)n);   // the partial block-row
+}
+
+// The weight with its rows in the given order (whole units, see above), as a canonical form of its own.
+void bsr_permute_rows(const Bsr& b, const std::vector<int32_t>& row_order, Bsr& out)
+{
+    const int unit_rows = (b.block == SPMM_BLOCK_N4K1) ? 4 : 1;
+    out.N = b.N; out.K = b.K; out.block = b.block; out.block_rows = b.block_rows;
+    out.row_ptr.assign(1, 0);
+    out.index.clear(); out.vals.clear();
+    out.index.reserve(b.index.size()); out.vals.reserve(b.vals.size());
+    for (int64_t br = 0; br < b.block_rows; ++br) {
+        const int64_t src = row_order[(size_t)(br * unit_rows)] / unit_rows;
+        out.index.insert(out.index.end(), b.index.begin() + b.row_ptr[src], b.index.begin() + b.row_ptr[src + 1]);
+        out.vals.insert(out.vals.end(), b.vals.begin() + 4 * b.row_ptr[src], b.vals.begin() + 4 * b.row_ptr[src + 1]);
+        out.row_ptr.push_back((int64_t)out.index.size());
+    }
+}
+
 void layout_from_bsr(const Bsr& b, int kc, HostLayout& out)
 {
     const int64_t N = b.N, K = b.K;

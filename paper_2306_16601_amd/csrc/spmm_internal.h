@@ -57,6 +57,10 @@ struct Bsr {
 void bsr_from_dense(const int8_t* W, int64_t N, int64_t K, int64_t ldw, spmm_block_t block, Bsr& out);
 void bsr_to_dense(const Bsr& b, int8_t* W, int64_t ldw);
 void layout_from_bsr(const Bsr& b, int kc, HostLayout& out);
+// row_order[i] = row of the weight that becomes row i (a permutation of 0..N-1 that moves whole
+// block-rows), chosen so that rows with overlapping k lists share a row tile
+void order_rows_by_k_overlap(const Bsr& b, int kc, std::vector<int32_t>& row_order);
+void bsr_permute_rows(const Bsr& b, const std::vector<int32_t>& row_order, Bsr& out);
 
 // ---------------------------------------------------------------------------------------
 // Kernel launch interface (plan and dispatch in spmm_plan.hip, kernels in spmm_kernels.h).

@@ -583,3 +583,31 @@ def test_info_reports_device_bytes_and_plan():
         assert tm > 0 and rows % 16 == 0 and wgs * tm * rows >= 6144 * N
     finally:
         sp.spmm_destroy(h)
+
+
+# ------------------------------------------------ offline row ordering (Section 3.2)
+@pytest.mark.parametrize("orient,N,K,M,s,clusters,out_type,postop", [
+    (wl.N4K1, 512, 1024, 700, 0.9, 8, "s8", "gelu"), (wl.N4K1, 1024, 1024, 1536, 0.8, 16, "f32", "none"),
+    (wl.N4K1, 130, 600, 333, 0.8, 3, "s32", "none"), (wl.N1K4, 256, 1024, 384, 0.9, 4, "u8", "none"),
+    (wl.N4K1, 768, 3072, 32, 0.9, 6, "f32", "gelu")])
+def test_reordered_rows_are_the_oracles_rows_in_the_reported_order(orient, N, K, M, s, clusters, out_type, postop):
+    """A weight packed with SPMM_PACK_REORDER_ROWS computes the rows of the product in the order
+    spmm_row_order reports, with the per-row operands read in that order."""
+    case = wl.Case("reordered", N, K, M, s, orient, out_type, postop, jitter=0.2, keys=(81, N, K, M), clusters=clusters)
+    d = wl.make(case)
+    ref = oracle_spmm(d["W"], d["X"], d, case)
+    h = sp.spmm_pack_ex(d["W"], orient, reorder_rows=True)
+    try:
+        order = sp.spmm_row_order(h)
+        assert sorted(order.tolist()) == list(range(N))
+        lut = None
+        if postop == "gelu" and out_type in ("s8", "u8"):
+            lut = dev(sp.spmm_make_gelu_lut(d["mid_scale"], d["out_scale"], d["out_zero_point"], out_type))
+        ep = sp.make_epilogue(dev(d["w_scale"][order]), d["x_scale"], d["x_zero_point"], dev(d["bias"][order]), postop,
+                              out_type, d["out_scale"], d["out_zero_point"], d["mid_scale"], lut)
+        out = torch.zeros((N, M), dtype=TORCH_DT[out_type], device="cuda")
+        sp.spmm_run(h, dev(d["X"]), M, M, ep, out, M, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert_parity(out.cpu().numpy(), np.ascontiguousarray(ref[order]), case)
+    finally:
+        sp.spmm_destroy(h)

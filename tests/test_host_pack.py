@@ -271,3 +271,71 @@ def test_plan_picks_token_tile_and_waves_per_shape():
     assert kernel(768, 3072, 6144) == "void spmm::spmm_rowtile_mfma<96, 16, 4, 2, 1>(spmm::KernelArgs)"
     assert kernel(4096, 1024, 6144) == "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)"
     assert plan(768, 768, 128, 0.9, (128, 8)) == (128, 128, 6)
+
+
+# ---- offline row ordering (Section 3.2: the blocking is tunable offline) -------------------------
+
+ORDER_CASES = [("n4k1", 256, 256, 0.9, 0), ("n1k4", 256, 256, 0.9, 0), ("n4k1", 50, 70, 0.5, 0),
+               ("n4k1", 3, 5, 0.0, 0), ("n1k4", 37, 131, 0.7, 0), ("n4k1", 512, 1024, 0.9, 8),
+               ("n1k4", 128, 1024, 0.9, 4), ("n4k1", 130, 600, 0.8, 3)]
+
+
+@pytest.mark.parametrize("orient,N,K,s,clusters", ORDER_CASES)
+def test_reordered_pack_is_a_block_row_permutation_and_round_trips(orient, N, K, s, clusters):
+    W = wl.sparse_weight(N, K, s, orient, jitter=0.2, keys=(78, N, K), clusters=clusters)
+    plain = sp.spmm_pack_host(W, orient)
+    h = sp.spmm_pack_ex(W, orient, host_only=True, reorder_rows=True)
+    try:
+        order = sp.spmm_row_order(h)
+        assert sorted(order.tolist()) == list(range(N))                    # a permutation of the rows
+        if orient == "n4k1":                                               # ... that moves whole block-rows
+            full = N // 4 * 4
+            blocks = order[:full].reshape(-1, 4)
+            assert np.all(blocks[:, 0] % 4 == 0) and np.all(blocks == blocks[:, :1] + np.arange(4))
+            assert np.array_equal(order[full:], np.arange(full, N))        # the partial block-row stays last
+        assert np.array_equal(sp.spmm_unpack(h), W)                        # unpack: the matrix as given
+        assert np.array_equal(sp.spmm_row_order(plain), np.arange(N))
+        # the handle IS the plain packing of the row-permuted matrix, bit for bit
+        ref = sp.spmm_pack_host(np.ascontiguousarray(W[order]), orient)
+        try:
+            assert sp.spmm_layout_dims(h) == sp.spmm_layout_dims(ref)
+            for a, b in zip(sp.spmm_layout_export(h), sp.spmm_layout_export(ref)):
+                assert np.array_equal(a, b)
+        finally:
+            sp.spmm_destroy(ref)
+        # ... and its layout replays to the oracle's accumulator of the permuted rows
+        X = wl.activations(K, 24, keys=(78, N, K))
+        assert np.array_equal(decode_layout_acc(h, X), oracle.acc_s32(W, X).astype(np.int64)[order])
+        assert sp.spmm_info(h)[2] == sp.spmm_info(plain)[2]                # same non-zero blocks
+    finally:
+        sp.spmm_destroy(h)
+        sp.spmm_destroy(plain)
+
+
+def test_reordering_finds_planted_clusters():
+    """Block-rows that follow 8 prototype patterns, in random order: after clustering a row tile
+    multiplies little more than one pattern instead of the union of four."""
+    W = wl.sparse_weight(1024, 1024, 0.9, "n4k1", keys=(79,), clusters=8)
+    plain = sp.spmm_pack_host(W)
+    h = sp.spmm_pack_ex(W, host_only=True, reorder_rows=True)
+    try:
+        assert sp.spmm_info(h)[3] <= 0.65 * sp.spmm_info(plain)[3]
+    finally:
+        sp.spmm_destroy(h)
+        sp.spmm_destroy(plain)
+    # and never makes a uniformly random pattern worse
+    W = wl.sparse_weight(1024, 1024, 0.9, "n4k1", jitter=0.2, keys=(80,))
+    plain = sp.spmm_pack_host(W)
+    h = sp.spmm_pack_ex(W, host_only=True, reorder_rows=True)
+    try:
+        assert sp.spmm_info(h)[3] <= sp.spmm_info(plain)[3]
+    finally:
+        sp.spmm_destroy(h)
+        sp.spmm_destroy(plain)
+
+
+def test_pack_ex_rejects_unknown_flags():
+    W = np.zeros((8, 8), dtype=np.int8)
+    h = ctypes.c_void_p()
+    rc = sp.lib().spmm_pack_ex(W.ctypes.data_as(ctypes.c_void_p), 8, 8, 8, 0, 4, ctypes.byref(h))
+    assert rc == 1 and not h.value

@@ -34,7 +34,7 @@ OUT_S32, OUT_F32, OUT_S8, OUT_U8 = "s32", "f32", "s8", "u8"
 POST_NONE, POST_GELU = "none", "gelu"
 
 # Tensor ids for the per-tensor random sub-streams.
-_T_W, _T_X, _T_WSCALE, _T_BIAS, _T_JITTER = 1, 2, 3, 4, 5
+_T_W, _T_X, _T_WSCALE, _T_BIAS, _T_JITTER, _T_CLUSTER = 1, 2, 3, 4, 5, 6
 
 X_SCALE = 0.02  # scalar activation scale used by every config
 
@@ -69,7 +69,7 @@ def block_counts(n_units: int, positions: int, density: float, jitter: float,
 
 
 def sparse_weight(N: int, K: int, sparsity: float, orientation: str = N4K1,
-                  jitter: float = 0.0, keys: Tuple[int, ...] = ()) -> np.ndarray:
+                  jitter: float = 0.0, keys: Tuple[int, ...] = (), clusters: int = 0) -> np.ndarray:
     """int8 [N, K] weight pruned in constant 4x1 blocks.
 
     N4K1: a block covers output rows 4b..4b+3 at one k; each block-row (4 rows)
@@ -79,6 +79,10 @@ def sparse_weight(N: int, K: int, sparsity: float, orientation: str = N4K1,
     Kept blocks are filled with values uniform in [-127, 127] without 0.
     N (N4K1) or K (N1K4) need not be multiples of 4: the last, partial block
     row/column is treated as a block of fewer elements.
+
+    clusters > 0 gives the pattern a structure that an offline row ordering can find: that
+    many prototype position sets are drawn, every block-row (in random order) follows one of
+    them, keeping about 90 % of its positions and drawing the rest at random.
     """
     density = 1.0 - sparsity
     rng_w = rng_for(*keys, _T_W)
@@ -92,7 +96,18 @@ def sparse_weight(N: int, K: int, sparsity: float, orientation: str = N4K1,
         raise ValueError(orientation)
     counts = block_counts(units, positions, density, jitter, rng_j)
     # random position order per unit: rank of uniform keys
-    order = np.argsort(rng_w.random((units, positions)), axis=1)
+    rank_key = rng_w.random((units, positions))
+    if clusters > 0:
+        rng_c = rng_for(*keys, _T_CLUSTER)
+        proto_count = min(positions, round_half_up(density * positions))
+        proto_order = np.argsort(rng_c.random((clusters, positions)), axis=1)
+        member = np.zeros((clusters, positions), dtype=bool)
+        np.put_along_axis(member, proto_order[:, :proto_count], True, axis=1)
+        follows = rng_c.integers(0, clusters, size=units)
+        dropped = rng_c.random((units, positions)) < 0.1
+        # positions of the followed prototype (minus the dropped tenth) rank before all others
+        rank_key = rank_key + np.where(member[follows] & ~dropped, 0.0, 1.0)
+    order = np.argsort(rank_key, axis=1)
     keep = np.zeros((units, positions), dtype=bool)
     cols = np.arange(positions)[None, :]
     np.put_along_axis(keep, order, cols < counts[:, None], axis=1)
@@ -154,6 +169,7 @@ class Case:
     x_zero_point: int = 0
     out_zero_point: int = 0
     keys: Tuple[int, ...] = field(default_factory=tuple)
+    clusters: int = 0
 
     def with_(self, **kw) -> "Case":
         return replace(self, **kw)
@@ -161,7 +177,7 @@ class Case:
 
 def make(case: Case) -> Dict[str, object]:
     """Draw every input tensor of `case` (host numpy arrays + scalar params)."""
-    W = sparse_weight(case.N, case.K, case.sparsity, case.orientation, case.jitter, case.keys)
+    W = sparse_weight(case.N, case.K, case.sparsity, case.orientation, case.jitter, case.keys, case.clusters)
     X = activations(case.K, case.M, case.keys)
     w_scale, bias = channel_params(case.N, case.keys)
     mid_scale, out_scale = quant_scales(case.K, case.sparsity)
@@ -276,6 +292,17 @@ def large_cases(orientation: str = N4K1, sparsities=(0.90, 0.80), M: int = 16 * 
 
 GRID_DIMS = (256, 512, 768, 1024, 2048, 3072, 4096)
 GRID_M = (128, 384, 1024, 4096)
+
+
+def clustered_cases(orientation: str = N4K1, clusters: int = 32, M: int = 16 * 384) -> List[Case]:
+    """The 4096x1024 BERT-Large layer at 90 and 80 % with block-rows that follow `clusters`
+    prototype patterns in random order (exercise for offline row ordering; not one of the five
+    configurations: pruned checkpoints are not available, this only shows what structure is worth)."""
+    out = []
+    for s in (0.90, 0.80):
+        out.append(Case("clustered%d_4096x1024_m%d_s%d" % (clusters, M, _pct(s)), 4096, 1024, M, s, orientation,
+                        OUT_S8, POST_GELU, keys=(6, 4096, 1024, M, _pct(s), clusters), clusters=clusters))
+    return out
 
 
 def grid_shapes() -> List[Tuple[int, int]]:
