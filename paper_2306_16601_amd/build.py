@@ -20,6 +20,8 @@ HOST_SOURCES = ["api.cpp", "pack.cpp", "spmm_plan.hip", "spmm_peak.hip"]
 # (token tile, waves, step slots) of the pipelined kernel; row tiles per wave of the simple kernel
 PIPELINED = [(128, 16, 4), (128, 16, 5), (128, 16, 6), (128, 8, 4), (128, 8, 6), (128, 8, 8),
              (96, 16, 4), (96, 16, 5), (96, 16, 6)]
+# (token tile, compute waves, step slots) of the pipelined kernel with 4 loader waves
+FED = [(128, 12, 4), (128, 12, 6), (128, 8, 4), (128, 8, 6), (128, 8, 8), (96, 12, 4), (96, 12, 6)]
 SIMPLE = [1, 2]
 SLAB = [16, 32]            # token tiles of the short-batch kernel
 STREAM = [64, 32, 16]      # token tiles of the streamed kernel
@@ -42,6 +44,8 @@ def units():
     cfg = os.path.join(CSRC, "spmm_launch_cfg.hip")
     for tm, nw, maxs in PIPELINED:
         out.append((f"cfg_{tm}_{nw}_{maxs}.o", cfg, [f"-DSPMM_CFG_TM={tm}", f"-DSPMM_CFG_NW={nw}", f"-DSPMM_CFG_MAXS={maxs}"]))
+    for tm, nw, maxs in FED:
+        out.append((f"cfg_fed_{tm}_{nw}_{maxs}.o", cfg, [f"-DSPMM_CFG_FED_TM={tm}", f"-DSPMM_CFG_NW={nw}", f"-DSPMM_CFG_MAXS={maxs}"]))
     for r in SIMPLE:
         out.append((f"cfg_simple_{r}.o", cfg, [f"-DSPMM_CFG_SIMPLE={r}"]))
     for tm in SIMPLE_NARROW:
@@ -81,7 +85,7 @@ def build(force: bool = True, verbose: bool = False, jobs: int | None = None) ->
     try:
         us = units()
         # the heaviest objects (pipelined kernels) first
-        us.sort(key=lambda u: 0 if u[0].startswith("cfg_1") or u[0].startswith("cfg_9") else 1)
+        us.sort(key=lambda u: 0 if u[0].startswith("cfg_1") or u[0].startswith("cfg_9") or u[0].startswith("cfg_fed") else 1)
         cmds = [[hipcc, *HIPCC_FLAGS, *defs, "-x", "hip", "-c", src, "-o", os.path.join(objdir, obj)]
                 for obj, src, defs in us]
         with ThreadPoolExecutor(max_workers=jobs) as pool:

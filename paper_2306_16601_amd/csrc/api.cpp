@@ -55,11 +55,11 @@ void free_device(spmm_handle* h)
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-spmm::Plan plan_for(const spmm_handle* h, int64_t M, bool aligned = true)
+spmm::Plan plan_for(const spmm_handle* h, int64_t M, bool aligned = true, int out_bytes = 1)
 {
     const spmm::WeightDims w{h->ntiles, h->nseg, (int)h->bsr.K, h->nsteps, h->max_steps_per_segment,
                              h->max_steps_per_tile};
-    return spmm::make_plan(M, w, h->num_cus, h->force_tm, h->force_r, aligned);
+    return spmm::make_plan(M, w, h->num_cus, h->force_tm, h->force_r, aligned, out_bytes);
 }
 
 }  // namespace
@@ -194,10 +194,9 @@ spmm_status_t spmm_plan(const spmm_handle_t* h, int64_t M, spmm_out_t out_type, 
                         int32_t* rows_per_workgroup, int64_t* workgroups)
 {
     if (!h || M <= 0) return SPMM_E_ARG;
-    const spmm::Plan p = plan_for(h, M);
+    const spmm::Plan p = plan_for(h, M, true, (out_type == SPMM_OUT_S32 || out_type == SPMM_OUT_F32) ? 4 : 1);
     if (token_tile) *token_tile = p.token_tile;
     if (rows_per_workgroup) *rows_per_workgroup = p.waves * p.row_tiles_per_wave * spmm::TILE_ROWS;
-    (void)out_type;
     if (workgroups) *workgroups = p.workgroups;
     return SPMM_OK;
 }
@@ -272,7 +271,7 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
                        (h->bsr.N * ep->ld_sum * 4 < ((int64_t)1 << 31));
     }
 
-    const spmm::Plan p = plan_for(h, M, a.x_vec_ok && a.out_vec_ok);
+    const spmm::Plan p = plan_for(h, M, a.x_vec_ok && a.out_vec_ok, (int)esz);
     const int rc = spmm::launch_spmm(p, a, ot, (gelu ? SPMM_POST_GELU : SPMM_POST_NONE) | (ep->sum ? spmm::POST_SUM_BIT : 0),
                                      hip_stream);
     return rc == 0 ? SPMM_OK : SPMM_E_DEVICE;
@@ -305,7 +304,7 @@ spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t 
     if (out_type < SPMM_OUT_S32 || out_type > SPMM_OUT_U8) return SPMM_E_ARG;
     if (postop != SPMM_POST_NONE && postop != SPMM_POST_GELU && postop != SPMM_POST_TABLE) return SPMM_E_ARG;
     if (postop == SPMM_POST_TABLE) postop = SPMM_POST_GELU;   // same kernels
-    const spmm::Plan p = plan_for(h, M);
+    const spmm::Plan p = plan_for(h, M, true, (out_type == SPMM_OUT_S32 || out_type == SPMM_OUT_F32) ? 4 : 1);
     const int post = (out_type == SPMM_OUT_S32) ? 0 : (int)postop;   // S32 output ignores the post-operator
     if (p.stream)
         std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_stream<%d, %d, %d, %d>(spmm::KernelArgs)",
@@ -316,6 +315,9 @@ spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t 
     else if (p.simple)
         std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_simple<%d, %d, %d, %d, %d>(spmm::KernelArgs)",
                       p.token_tile, p.waves, p.row_tiles_per_wave, (int)out_type, post);
+    else if (p.loaders)
+        std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma_fed<%d, %d, %d, %d, %d, %d>(spmm::KernelArgs)",
+                      p.token_tile, p.waves, p.loaders, p.max_steps, (int)out_type, post);
     else
         // (8-wave configurations run 5-step weights with the 6-step instantiation)
         std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma<%d, %d, %d, %d, %d>(spmm::KernelArgs)",

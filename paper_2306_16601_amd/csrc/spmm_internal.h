@@ -93,7 +93,8 @@ struct KernelArgs {
 struct Plan {
     int token_tile;          // TM of the pipelined kernel (128 or 96), or 64 for the simple kernel
     int row_tiles_per_wave;  // 1 (pipelined) or 1 / 2 (simple kernel)
-    int waves;               // NW
+    int waves;               // NW: waves that own a row tile
+    int loaders;             // pipelined kernel: extra waves that only stage activations (0 or 4)
     int simple;              // 1: simple kernel
     int slab;                // 1: the short-batch kernel (token tile 16 or 32, whole K resident in LDS) in its place
     int stream;              // 1: the streamed kernel (segment staging, flat weight stream) in its place
@@ -103,6 +104,7 @@ struct Plan {
 };
 
 // variant: 0 = automatic, 8 / 16 = waves per workgroup (pipelined, token tile 128 or 96),
+// 108 / 112 = pipelined with 8 / 12 compute waves and 4 loader waves (token tile 128; 112 also 96),
 // 101 / 102 = simple kernel with 1 / 2 row tiles per wave (token tile 64; 101 also 32 and 16),
 // 103 = short-batch kernel (token tile 16 or 32), 104 = streamed kernel (token tile 64, 32 or 16)
 constexpr int SLAB_SEGMENTS = 8;      // K segments the short-batch kernel keeps in LDS, token tile 16
@@ -116,7 +118,9 @@ struct WeightDims {
 bool plan_supported(int token_tile, int variant);
 // aligned: X and out take the 16-byte paths (base and row pitch aligned); if not, the automatic choice
 // avoids the 16-wave pipelined kernels, whose general paths are the slow bytewise ones
-Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant, bool aligned = true);
+// out_bytes: size of an output element (the plan gives 4-byte outputs workgroups with loader waves)
+Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant, bool aligned = true,
+               int out_bytes = 1);
 // Launches the SpMM kernel; returns a hipError_t value as int (0 = success).
 // postop: SPMM_POST_* value, plus POST_SUM_BIT when a.sum is to be added
 constexpr int POST_SUM_BIT = 4;   // (a bit no SPMM_POST_* value uses)

@@ -610,6 +610,206 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
     }
 }
 
+// =======================================================================================
+// Pipelined persistent kernel with loader waves: the same decomposition, LDS geometry and
+// phases as spmm_rowtile_mfma, but the workgroup is NW compute waves (one row tile each)
+// plus LW = 4 waves that do nothing but stage the activations.
+//
+// Why: on this architecture loads and stores of a wave share one completion counter and may
+// complete out of order with each other, so a wave that has stored a tile's outputs cannot
+// wait for its next activation loads without also waiting until the stores have reached
+// memory.  In spmm_rowtile_mfma every wave does both, and for 4-byte outputs (the downconvert
+// of Section 3.3 left out: 4 N M bytes) the whole workgroup then stands still at the next
+// commit until the burst of stores has drained.  Here the waves that store never load
+// activations (with at most two K segments they load nothing at all after start-up), and the
+// waves that load never store: the stores of tile j drain while tile j + 1 is multiplied.
+//
+// Loader wave: at the start of phase p its registers hold the activations of phase p + 1
+// (requested a whole phase earlier); it writes them to buffer (p + 1) % 2, whose readers
+// finished before the last barrier, requests phase p + 2 and goes to the barrier.
+// Compute wave: multiply out of buffer p % 2, post-operators after the last segment, barrier.
+// Both kinds pass exactly 1 + phases barriers.
+// =======================================================================================
+template <int TM, int NW, int LW, int MAXS, int OUT, int POST>
+__global__ void __launch_bounds__((NW + LW) * 64) spmm_rowtile_mfma_fed(const KernelArgs a)
+{
+    using G = Geo<TM>;
+    constexpr int PIECES = G::PIECES;
+    constexpr int LTHREADS = LW * 64;
+    constexpr int ROWS_PER_PASS = 32;
+    constexpr int STAGERS = ROWS_PER_PASS * PIECES;              // 256 (128 tokens) or 192 (96 tokens)
+    constexpr int XLOADS = SEGMENT_ROWS / ROWS_PER_PASS;         // 16-byte loads per staging thread and phase
+    static_assert(STAGERS <= LTHREADS, "the loader waves must cover one pass of rows");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[G::LDS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+
+    // workgroup -> (token-tile stream, row group): as in spmm_rowtile_mfma
+    const int S = a.n_streams;
+    int stream = (a.xcd_map == 2) ? blockIdx.y : blockIdx.x;
+    const int rg = (a.xcd_map == 2) ? blockIdx.x : blockIdx.y;
+    if (a.xcd_map == 1) stream = (stream & 7) * (S >> 3) + (stream >> 3);
+    const int n_my = a.tiles_per_stream + (stream < a.tiles_extra ? 1 : 0);
+    const int total = n_my * a.nseg;                                          // phases
+    constexpr bool TABLE = (POST & SPMM_POST_GELU) != 0 && (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8);
+
+    if (wave >= NW) {
+        // ------------------------------------------------------------------ loader wave
+        const int ltid = tid - NW * 64;
+        const bool stager = ltid < STAGERS;
+        const int x_row0 = ltid / PIECES, x_piece = ltid % PIECES;
+        const uint32_t x_lds0 = G::X0 + (uint32_t)x_row0 * G::STRIDE + x_piece * 16;
+        v4i xr[XLOADS];
+        auto x_issue = [&](const int q) {
+            const int j = q / a.nseg, seg = q - j * a.nseg;
+            const int tok0 = (stream + j * S) * TM;
+            const int k0 = seg * SEGMENT_ROWS;
+            const int last = min(SEGMENT_ROWS, a.K - k0) - 1;   // rows past K repeat the last one (never multiplied)
+            if (!stager) return;
+            if (a.x_vec_ok && tok0 + TM <= a.M) {
+                const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0;
+#pragma unroll
+                for (int u = 0; u < XLOADS; ++u) {
+                    const int row = min(x_row0 + u * ROWS_PER_PASS, last);
+                    xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(x_piece * 16)));
+                }
+            } else if (a.x_vec_ok) {
+                // ragged last tile of an aligned matrix: a piece is whole, beyond the end, or cut by it;
+                // the cut one is read whole (it lies inside the row pitch) and masked
+                const uint8_t* src = a.X + (int64_t)k0 * a.ldx;
+                const int col = tok0 + x_piece * 16;
+                const bool in = col < a.M;
+                const v4i mask = piece_mask(a.M - col);
+#pragma unroll
+                for (int u = 0; u < XLOADS; ++u) {
+                    const int row = min(x_row0 + u * ROWS_PER_PASS, last);
+                    xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(in ? col : 0))) & mask;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < XLOADS; ++u) {
+                    const int row = min(x_row0 + u * ROWS_PER_PASS, last);
+                    xr[u] = load_x16(a, k0 + row, tok0 + x_piece * 16);
+                }
+            }
+        };
+        auto x_commit = [&](const int q) {
+            if (!stager) return;
+            uint8_t* buf = lds + (q & 1) * G::BUF + x_lds0;
+#pragma unroll
+            for (int u = 0; u < XLOADS; ++u)
+                *(v4i*)(buf + u * ROWS_PER_PASS * G::STRIDE) = xr[u] ^ (v4i){FLIP, FLIP, FLIP, FLIP};
+        };
+        x_issue(0);
+        int table_byte = 0;
+        if constexpr (TABLE) table_byte = a.lut[ltid];          // LTHREADS == 256 entries
+        x_commit(0);
+        if constexpr (TABLE) lds[G::lut_addr(ltid)] = (uint8_t)table_byte;
+        if (1 < total) x_issue(1);
+        __syncthreads();
+        for (int p = 0; p < total; ++p) {
+            if (p + 1 < total) x_commit(p + 1);
+            if (p + 2 < total) x_issue(p + 2);
+            __syncthreads();
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- compute wave
+    const int tile = rg * NW + wave;
+    const bool have_tile = tile < a.ntiles;
+    const int n = tile * TILE_ROWS + c;                       // this lane's output row
+    int init = 0;
+    float scale = 0.0f, bias = 0.0f;
+    v4i A0[MAXS], A1[MAXS];
+    uint32_t I0[MAXS], I1[MAXS];
+    int n0 = 0, n1 = 0;
+    v4i acc[PIECES];
+
+    auto w_issue = [&](const int q, v4i (&A)[MAXS], uint32_t (&I)[MAXS], int& cnt) {
+        cnt = 0;
+        int s0 = 0;
+        if (have_tile) {
+            const int seg = q % a.nseg;
+            s0 = a.seg_ptr[tile * a.nseg + seg];
+            cnt = a.seg_ptr[tile * a.nseg + seg + 1] - s0;
+        }
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) {
+            const int step = (s < cnt) ? s0 + s : 0;           // unused slots re-read step 0
+            A[s] = *(const v4i*)(a.vals + (int64_t)step * STEP_VAL_BYTES + lane * 16);
+            I[s] = a.idx[(int64_t)step * STEP_IDX_DWORDS + 8 * g + (c >> 1)];
+        }
+    };
+    auto multiply = [&](const int q, const v4i (&A)[MAXS], const uint32_t (&I)[MAXS], const int cnt) {
+        const uint32_t base = G::X0 + (uint32_t)(q & 1) * G::BUF + (c & 1) * 8;
+#pragma unroll
+        for (int s = 0; s < MAXS; ++s) {
+            if (s < cnt) {
+                const uint32_t a0 = (I[s] & 0xffffu) * G::STRIDE + base;
+                const uint32_t a1 = (I[s] >> 16) * G::STRIDE + base;
+#pragma unroll
+                for (int i = 0; i < PIECES; ++i) {
+                    const v2i x0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a0 + 16 * i));
+                    const v2i x1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i_ptr)(lds + a1 + 16 * i));
+                    const v4i xa = {x0[0], x0[1], x1[0], x1[1]};
+                    acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa, A[s], acc[i], 0, 0, 0);
+                }
+            }
+        }
+    };
+    auto finish = [&](const int q) {
+        const int j = q / a.nseg;
+        if (q - j * a.nseg != a.nseg - 1) return;
+        const int tok0 = (stream + j * S) * TM;
+        if (have_tile) {
+            if (a.out_vec_ok && tok0 + TM <= a.M) {
+                finish_tile_fast<TM, OUT, POST>(a, acc, scale, bias, tile, tok0, lane, wave, lds);
+            } else if (n < a.N) {
+                const LdsLut<TM> lut{lds};
+#pragma unroll
+                for (int i = 0; i < PIECES; ++i) {
+                    const int m0 = tok0 + 16 * i + 4 * g;
+                    if (m0 < a.M) finish4<OUT, POST, false>(a, acc[i], scale, bias, n, m0, lut);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
+    };
+    const bool reload = a.nseg > 2;   // otherwise register set q % 2 always holds segment q % nseg
+
+    w_issue(0, A0, I0, n0);
+    if (have_tile) init = a.rowsum[n] * a.corr_mul;
+    if constexpr (OUT != SPMM_OUT_S32) {
+        if (have_tile && n < a.N) {
+            scale = a.w_scale[n] * a.x_scale;
+            if (a.bias) bias = a.bias[n];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) acc[i] = (v4i){init, init, init, init};
+    __syncthreads();
+    for (int p = 0; p < total; p += 2) {
+        {   // even phase: register set 0, LDS buffer 0
+            if (p + 1 < total && (reload || p + 1 < 2)) w_issue(p + 1, A1, I1, n1);
+            multiply(p, A0, I0, n0);
+            finish(p);
+            __syncthreads();
+        }
+        if (p + 1 >= total) break;
+        {   // odd phase: register set 1, LDS buffer 1
+            if (p + 2 < total && reload) w_issue(p + 2, A0, I0, n0);
+            multiply(p + 1, A1, I1, n1);
+            finish(p + 1);
+            __syncthreads();
+        }
+    }
+}
+
 // Workgroup id -> (token tile, row group) of the simple and short-batch kernels.  Ids go round the
 // 8 XCDs; map 1 keeps the workgroups of a token tile on one XCD, map 2 those of a row group (the
 // host picks the one that slices the larger operand over the L2s).  False: a padding workgroup.

@@ -5,6 +5,7 @@
 //                      -DSPMM_CFG_SIMPLE=1 -DSPMM_CFG_SIMPLE_TM=<32|16>
 //   short-batch kernel: -DSPMM_CFG_SLAB=<16|32>      (token tile)
 //   streamed kernel  : -DSPMM_CFG_STREAM=<64|32|16>  (token tile)
+//   loader-fed pipelined kernel: -DSPMM_CFG_FED_TM=<128|96> -DSPMM_CFG_NW=<12|8> -DSPMM_CFG_MAXS=<4|6|8>
 // Each defines one function launch_cfg_<...>() that picks the epilogue instantiation and
 // launches it; spmm_plan.hip calls them.
 #include "spmm_kernels.h"
@@ -47,7 +48,25 @@ static void dispatch_epilogue(spmm_out_t out_type, int postop, dim3 grid, dim3 b
 // different instantiations: internal linkage keeps the linker from folding their member functions
 // into one (which would launch the wrong kernel for every configuration but the one it kept).
 
-#if defined(SPMM_CFG_STREAM)
+#if defined(SPMM_CFG_FED_TM)
+namespace {
+template <int TM, int NW, int MAXS>
+struct FedLaunch {
+    template <int OUT, int POST>
+    static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
+    {
+        hipLaunchKernelGGL((spmm_rowtile_mfma_fed<TM, NW, 4, MAXS, OUT, POST>), grid, block, 0, st, a);
+    }
+};
+}  // namespace
+
+void SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(SPMM_CAT(launch_cfg_fed_, SPMM_CFG_FED_TM), _), SPMM_CFG_NW), _), SPMM_CFG_MAXS)(
+    spmm_out_t out_type, int postop, unsigned grid_x, unsigned grid_y, unsigned block, void* stream, const KernelArgs& a)
+{
+    dispatch_epilogue<FedLaunch<SPMM_CFG_FED_TM, SPMM_CFG_NW, SPMM_CFG_MAXS>>(out_type, postop, dim3(grid_x, grid_y),
+                                                                               dim3(block), (hipStream_t)stream, a);
+}
+#elif defined(SPMM_CFG_STREAM)
 namespace {
 struct StreamLaunch {
     template <int OUT, int POST>

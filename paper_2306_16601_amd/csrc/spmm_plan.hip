@@ -17,6 +17,13 @@ SPMM_DECLARE_CFG(launch_cfg_128_8_8);
 SPMM_DECLARE_CFG(launch_cfg_96_16_4);
 SPMM_DECLARE_CFG(launch_cfg_96_16_5);
 SPMM_DECLARE_CFG(launch_cfg_96_16_6);
+SPMM_DECLARE_CFG(launch_cfg_fed_128_12_4);
+SPMM_DECLARE_CFG(launch_cfg_fed_128_12_6);
+SPMM_DECLARE_CFG(launch_cfg_fed_128_8_4);
+SPMM_DECLARE_CFG(launch_cfg_fed_128_8_6);
+SPMM_DECLARE_CFG(launch_cfg_fed_128_8_8);
+SPMM_DECLARE_CFG(launch_cfg_fed_96_12_4);
+SPMM_DECLARE_CFG(launch_cfg_fed_96_12_6);
 SPMM_DECLARE_CFG(launch_cfg_simple_1);
 SPMM_DECLARE_CFG(launch_cfg_simple_2);
 SPMM_DECLARE_CFG(launch_cfg_simple32_1);
@@ -30,8 +37,8 @@ SPMM_DECLARE_CFG(launch_cfg_stream16);
 
 bool plan_supported(int token_tile, int variant)
 {
-    if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16;
-    if (token_tile == 96) return variant == 0 || variant == 16;
+    if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16 || variant == 108 || variant == 112;
+    if (token_tile == 96) return variant == 0 || variant == 16 || variant == 112;
     if (token_tile == 64) return variant == 101 || variant == 102 || variant == 104;
     if (token_tile == 32 || token_tile == 16) return variant == 101 || variant == 103 || variant == 104;
     return false;
@@ -43,6 +50,7 @@ static void fill_pipelined(Plan& p, int64_t M, int ntiles, int num_cus, int tm, 
 {
     p.token_tile = tm;
     p.waves = waves;
+    p.loaders = 0;
     p.row_tiles_per_wave = 1;
     p.simple = 0;
     p.slab = 0;
@@ -85,15 +93,18 @@ static void fill_simple(Plan& p, int64_t M, const WeightDims& w, int r, int tm)
 // when there are more workgroups than CUs.  An 8-wave workgroup stages the same activations for half
 // as many rows: measured, its token tile takes about two thirds of a 16-wave one (4096x1024, 90 %:
 // 33.0 against 25.5 us for twice the tiles).
+// With loader waves (4-byte outputs) a tile of 12 compute waves costs about 0.8 of a 16-wave one and one
+// of 8 compute waves about 0.6 (3072x768, 4096 tokens, fp32: 22.4 us with 192 workgroups of 16 waves,
+// 18.0 us with 256 of 12 + 4; 768x3072: 18.9 us with 8 waves, 16.2 us with 8 + 4 on the same grid).
 static double plan_cost(const Plan& p, int num_cus)
 {
     const int per_stream = (p.n_tok_tiles + p.n_streams - 1) / p.n_streams;
     const int64_t rounds = (p.workgroups + num_cus - 1) / num_cus;
-    const double per_token = (p.waves == 16) ? 1.0 : 0.66;
+    const double per_token = p.loaders ? (p.waves == 12 ? 0.8 : 0.6) : (p.waves == 16) ? 1.0 : 0.66;
     return (double)rounds * ((double)per_stream * (p.token_tile * per_token + 16.0) + 48.0);
 }
 
-Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant, bool aligned)
+Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int variant, bool aligned, int out_bytes)
 {
     const int ntiles = w.ntiles, nseg = w.nseg, max_steps_per_segment = w.max_steps_per_segment;
     Plan p{};
@@ -113,6 +124,14 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
     }
     if (force_tm == 64 || force_tm == 32 || force_tm == 16) {
         fill_simple(p, M, w, variant - 100, force_tm);
+        return p;
+    }
+    if (variant == 108 || variant == 112) {
+        // 12 compute waves have 128 registers each (at most 6 step slots); denser weights take 8
+        const int waves = (variant == 112 && max_steps <= 6 ) ? 12 : 8;
+        fill_pipelined(p, M, ntiles, num_cus, (waves == 12 && force_tm == 96) ? 96 : 128, waves);
+        p.loaders = 4;
+        if (p.max_steps == 5) p.max_steps = 6;
         return p;
     }
     // 16 waves have 128 registers each: at most 6 steps per segment; denser weights run with 8
@@ -140,6 +159,20 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
         c.max_steps = max_steps;
         fill_pipelined(c, M, ntiles, num_cus, 128, 8);
         if (plan_cost(c, num_cus) < plan_cost(p, num_cus)) p = c;
+    }
+    if (out_bytes == 4 && force_tm == 0 && variant == 0) {
+        // 4-byte outputs: the stores of a tile are 4 N M bytes and a wave that stores cannot wait for
+        // loads without waiting for them too; workgroups with loader waves keep multiplying meanwhile
+        Plan c{};
+        c.max_steps = (max_steps == 5) ? 6 : max_steps;
+        fill_pipelined(c, M, ntiles, num_cus, 128, 8);
+        c.loaders = 4;
+        if (p.waves == 8 || plan_cost(c, num_cus) < plan_cost(p, num_cus)) p = c;
+        if (max_steps <= 6) {
+            fill_pipelined(c, M, ntiles, num_cus, 128, 12);
+            c.loaders = 4;
+            if (plan_cost(c, num_cus) < plan_cost(p, num_cus)) p = c;
+        }
     }
     if (force_tm == 0 && variant == 0 && p.workgroups * 2 <= num_cus) {
         // Small problems (short batches): the persistent kernel cannot fill half the CUs; the
@@ -186,7 +219,7 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop
     a.n_row_groups = plan.n_row_groups;
     a.n_streams = plan.n_streams;
     a.xcd_map = plan.xcd_map;
-    const unsigned block = (unsigned)plan.waves * 64;
+    const unsigned block = (unsigned)(plan.waves + plan.loaders) * 64;
     if (plan.simple) {
         const unsigned grid = (unsigned)plan.workgroups;
         const int key = plan.token_tile * 10 + plan.row_tiles_per_wave;
@@ -215,6 +248,19 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop
     a.tiles_per_stream = plan.n_tok_tiles / plan.n_streams;
     a.tiles_extra = plan.n_tok_tiles % plan.n_streams;
     const int maxs = (plan.waves == 8 && plan.max_steps == 5) ? 6 : plan.max_steps;   // no 8-wave 5-step build
+    if (plan.loaders) {
+        switch (plan.token_tile * 10000 + plan.waves * 100 + maxs) {
+        case 1281204: launch_cfg_fed_128_12_4(out_type, postop, gx, gy, block, stream, a); break;
+        case 1281206: launch_cfg_fed_128_12_6(out_type, postop, gx, gy, block, stream, a); break;
+        case 1280804: launch_cfg_fed_128_8_4(out_type, postop, gx, gy, block, stream, a); break;
+        case 1280806: launch_cfg_fed_128_8_6(out_type, postop, gx, gy, block, stream, a); break;
+        case 1280808: launch_cfg_fed_128_8_8(out_type, postop, gx, gy, block, stream, a); break;
+        case 961204: launch_cfg_fed_96_12_4(out_type, postop, gx, gy, block, stream, a); break;
+        case 961206: launch_cfg_fed_96_12_6(out_type, postop, gx, gy, block, stream, a); break;
+        default: return (int)hipErrorInvalidValue;
+        }
+        return (int)hipGetLastError();
+    }
     switch (plan.token_tile * 10000 + plan.waves * 100 + maxs) {
     case 1281604: launch_cfg_128_16_4(out_type, postop, gx, gy, block, stream, a); break;
     case 1281605: launch_cfg_128_16_5(out_type, postop, gx, gy, block, stream, a); break;

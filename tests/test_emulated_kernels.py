@@ -49,6 +49,11 @@ CASES = [
     (256, 2048, 384, 0.9, "u8", "gelu", 128, 16, "spmm_rowtile_mfma<128, 16", {}),            # weights reloaded per phase
     (300, 1000, 333, 0.85, "s8", "none", 128, 0, "spmm_rowtile_mfma<", {"cus": 2}),            # ragged everything
     (128, 512, 200, 0.7, "s8", "gelu", 128, 8, "spmm_rowtile_mfma<128, 8", {"ldx": 211, "ldo": 203}),   # unaligned pitches
+    # pipelined kernel with loader waves: 12 + 4 and 8 + 4 waves, both tile widths, weights reloaded, ragged, unaligned
+    (400, 1024, 384, 0.9, "f32", "none", 128, 112, "spmm_rowtile_mfma_fed<128, 12", {"cus": 2}),
+    (272, 1536, 300, 0.8, "s32", "none", 128, 108, "spmm_rowtile_mfma_fed<128, 8", {"cus": 2}),
+    (400, 600, 333, 0.9, "s8", "gelu", 96, 112, "spmm_rowtile_mfma_fed<96, 12", {"cus": 2}),
+    (272, 700, 250, 0.8, "f32", "gelu", 128, 112, "spmm_rowtile_mfma_fed<128, 8", {"cus": 2, "ldx": 251, "ldo": 253, "kind": "ragged"}),
     # simple kernel at its three tile widths
     (256, 1024, 192, 0.9, "s8", "gelu", 64, 101, "spmm_rowtile_mfma_simple<64", {}),
     (512, 768, 128, 0.8, "s32", "none", 64, 102, "spmm_rowtile_mfma_simple<64", {}),

@@ -272,6 +272,24 @@ def test_plan_picks_token_tile_and_waves_per_shape():
     assert kernel(4096, 1024, 6144) == "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)"
     assert plan(768, 768, 128, 0.9, (128, 8)) == (128, 128, 6)
 
+    # 4-byte outputs: workgroups of 12 or 8 compute waves plus 4 loader waves
+    def kernel32(N, K, M, out_type="f32", tuning=None):
+        h = sp.spmm_pack_host(wl.sparse_weight(N, K, 0.9, keys=(81, N, K)))
+        try:
+            if tuning:
+                sp.spmm_set_tuning(h, *tuning)
+            return sp.spmm_kernel_variant(h, M, out_type, "none"), tuple(sp.spmm_plan(h, M, out_type))
+        finally:
+            sp.spmm_destroy(h)
+
+    assert kernel32(3072, 768, 4096) == ("void spmm::spmm_rowtile_mfma_fed<128, 12, 4, 4, 1, 0>(spmm::KernelArgs)",
+                                         (128, 192, 256))           # 16 row groups x 16 streams of 2 tiles
+    assert kernel32(768, 3072, 4096)[0] == "void spmm::spmm_rowtile_mfma_fed<128, 8, 4, 4, 1, 0>(spmm::KernelArgs)"
+    assert kernel32(768, 768, 4096, "s32")[0] == "void spmm::spmm_rowtile_mfma_fed<128, 8, 4, 4, 0, 0>(spmm::KernelArgs)"
+    assert kernel32(768, 768, 128)[0].startswith("void spmm::spmm_rowtile_mfma_simple<16")    # short batches: unchanged
+    assert kernel32(1024, 1024, 6144, "f32", (96, 112))[0] == "void spmm::spmm_rowtile_mfma_fed<96, 12, 4, 4, 1, 0>(spmm::KernelArgs)"
+    assert kernel32(1024, 1024, 6144, "f32", (128, 108))[1] == (128, 128, 256)
+
 
 # ---- offline row ordering (Section 3.2: the blocking is tunable offline) -------------------------
 
