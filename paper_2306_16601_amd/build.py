@@ -21,7 +21,7 @@ HOST_SOURCES = ["api.cpp", "pack.cpp", "spmm_plan.hip", "spmm_peak.hip"]
 PIPELINED = [(128, 16, 4), (128, 16, 5), (128, 16, 6), (128, 8, 4), (128, 8, 6), (128, 8, 8),
              (96, 16, 4), (96, 16, 5), (96, 16, 6)]
 # (token tile, compute waves, step slots) of the pipelined kernel with 4 loader waves
-FED = [(128, 12, 4), (128, 12, 6), (128, 8, 4), (128, 8, 6), (128, 8, 8), (96, 12, 4), (96, 12, 6)]
+FED = [(128, 12, 4), (128, 12, 6), (128, 8, 4), (128, 8, 6), (128, 8, 8), (96, 12, 4), (96, 12, 6), (64, 12, 4), (64, 12, 6)]
 SIMPLE = [1, 2]
 SLAB = [16, 32]            # token tiles of the short-batch kernel
 STREAM = [64, 32, 16]      # token tiles of the streamed kernel

@@ -281,6 +281,18 @@ struct Geo<96> {
     static __device__ __forceinline__ uint32_t chunk(uint32_t n) { return X0 + n * STRIDE + 96; }
 };
 
+// TM = 64 (loader-wave kernel only): four pieces per row, twice as many tiles per stream; the output
+// stores of a workgroup then start after half the time and the last tile's burst is half as long.
+template <>
+struct Geo<64> {
+    static constexpr int STRIDE = 80, PIECES = 4, HALVES = 1;
+    static constexpr int BUF = SEGMENT_ROWS * STRIDE;   // 40960
+    static constexpr int X0 = 256;
+    static constexpr int LDS = X0 + 2 * BUF;
+    static __device__ __forceinline__ uint32_t lut_addr(uint32_t key) { return key; }
+    static __device__ __forceinline__ uint32_t chunk(uint32_t n) { return X0 + n * STRIDE + 64; }
+};
+
 template <int TM>
 struct LdsLut {
     const uint8_t* lds;

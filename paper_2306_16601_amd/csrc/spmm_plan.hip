@@ -24,6 +24,8 @@ SPMM_DECLARE_CFG(launch_cfg_fed_128_8_6);
 SPMM_DECLARE_CFG(launch_cfg_fed_128_8_8);
 SPMM_DECLARE_CFG(launch_cfg_fed_96_12_4);
 SPMM_DECLARE_CFG(launch_cfg_fed_96_12_6);
+SPMM_DECLARE_CFG(launch_cfg_fed_64_12_4);
+SPMM_DECLARE_CFG(launch_cfg_fed_64_12_6);
 SPMM_DECLARE_CFG(launch_cfg_simple_1);
 SPMM_DECLARE_CFG(launch_cfg_simple_2);
 SPMM_DECLARE_CFG(launch_cfg_simple32_1);
@@ -39,7 +41,7 @@ bool plan_supported(int token_tile, int variant)
 {
     if (token_tile == 128) return variant == 0 || variant == 8 || variant == 16 || variant == 108 || variant == 112;
     if (token_tile == 96) return variant == 0 || variant == 16 || variant == 112;
-    if (token_tile == 64) return variant == 101 || variant == 102 || variant == 104;
+    if (token_tile == 64) return variant == 101 || variant == 102 || variant == 104 || variant == 112;
     if (token_tile == 32 || token_tile == 16) return variant == 101 || variant == 103 || variant == 104;
     return false;
 }
@@ -110,6 +112,13 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
     Plan p{};
     const int max_steps = max_steps_per_segment <= 4 ? 4 : (max_steps_per_segment <= 6 ? max_steps_per_segment : 8);
     p.max_steps = max_steps;
+    if (force_tm == 64 && variant == 112) {
+        // (weights with more than 6 steps per segment run 8 compute waves, which exist with 128-token tiles)
+        fill_pipelined(p, M, ntiles, num_cus, max_steps <= 6 ? 64 : 128, max_steps <= 6 ? 12 : 8);
+        p.loaders = 4;
+        if (p.max_steps == 5) p.max_steps = 6;
+        return p;
+    }
     if ((force_tm == 16 || force_tm == 32) && variant == 103) {
         // the short-batch kernel holds K <= 4096 (3072 with 32-token tiles); longer K silently runs
         // the simple kernel
@@ -169,7 +178,9 @@ Plan make_plan(int64_t M, const WeightDims& w, int num_cus, int force_tm, int va
         c.loaders = 4;
         if (p.waves == 8 || plan_cost(c, num_cus) < plan_cost(p, num_cus)) p = c;
         if (max_steps <= 6) {
-            for (int tm = 128; tm >= 96; tm -= 32) {   // (768x3072, 6144 tokens, 80 %: 28.5 us with 16 waves, 22.5 us with 12 + 4 and 96-token tiles)
+            // (768x3072, 6144 tokens, 80 %: 28.5 us with 16 waves, 22.5 us with 12 + 4 and 96-token tiles;
+            // 768x768, 4096 tokens: 9.3 us with 8 + 4 and 128-token tiles on 192 CUs, 8.3 us with 12 + 4 and 64-token tiles on 256)
+            for (int tm = 128; tm >= 64; tm -= 32) {
                 fill_pipelined(c, M, ntiles, num_cus, tm, 12);
                 c.loaders = 4;
                 if (plan_cost(c, num_cus) < plan_cost(p, num_cus)) p = c;
@@ -259,6 +270,8 @@ int launch_spmm(const Plan& plan, KernelArgs& a, spmm_out_t out_type, int postop
         case 1280808: launch_cfg_fed_128_8_8(out_type, postop, gx, gy, block, stream, a); break;
         case 961204: launch_cfg_fed_96_12_4(out_type, postop, gx, gy, block, stream, a); break;
         case 961206: launch_cfg_fed_96_12_6(out_type, postop, gx, gy, block, stream, a); break;
+        case 641204: launch_cfg_fed_64_12_4(out_type, postop, gx, gy, block, stream, a); break;
+        case 641206: launch_cfg_fed_64_12_6(out_type, postop, gx, gy, block, stream, a); break;
         default: return (int)hipErrorInvalidValue;
         }
         return (int)hipGetLastError();

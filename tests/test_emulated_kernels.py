@@ -54,6 +54,8 @@ CASES = [
     (272, 1536, 300, 0.8, "s32", "none", 128, 108, "spmm_rowtile_mfma_fed<128, 8", {"cus": 2}),
     (400, 600, 333, 0.9, "s8", "gelu", 96, 112, "spmm_rowtile_mfma_fed<96, 12", {"cus": 2}),
     (272, 700, 250, 0.8, "f32", "gelu", 128, 112, "spmm_rowtile_mfma_fed<128, 8", {"cus": 2, "ldx": 251, "ldo": 253, "kind": "ragged"}),
+    (272, 700, 250, 0.8, "s8", "gelu", 64, 112, "spmm_rowtile_mfma_fed<128, 8", {"cus": 2, "kind": "ragged"}),   # dense tile: falls back to 8 + 4
+    (200, 600, 203, 0.9, "u8", "none", 64, 112, "spmm_rowtile_mfma_fed<64, 12", {"cus": 2, "ldx": 211, "ldo": 209}),
     # simple kernel at its three tile widths
     (256, 1024, 192, 0.9, "s8", "gelu", 64, 101, "spmm_rowtile_mfma_simple<64", {}),
     (512, 768, 128, 0.8, "s32", "none", 64, 102, "spmm_rowtile_mfma_simple<64", {}),

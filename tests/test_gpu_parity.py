@@ -124,7 +124,7 @@ def test_config4_large_all_kernel_variants_agree_bitwise():
     case = wl.large_cases()[0]
     d = wl.make(case)
     a, _ = gpu_spmm(d["W"], d["X"], d, case)
-    for tuning in ((128, 0), (128, 8), (128, 16), (96, 0), (96, 16), (128, 112), (128, 108), (96, 112), (64, 101), (64, 102), (32, 101), (16, 101), (16, 103), (32, 103), (64, 104), (32, 104), (16, 104)):
+    for tuning in ((128, 0), (128, 8), (128, 16), (96, 0), (96, 16), (128, 112), (128, 108), (96, 112), (64, 112), (64, 101), (64, 102), (32, 101), (16, 101), (16, 103), (32, 103), (64, 104), (32, 104), (16, 104)):
         b, _ = gpu_spmm(d["W"], d["X"], d, case, tuning=tuning)
         assert np.array_equal(a, b), tuning
 
@@ -361,9 +361,9 @@ def test_config5_whole_grid_at_full_size(NK):
     (260, 100, 257), (5, 3000, 7),
 ])
 @pytest.mark.parametrize("out_type", ["s32", "s8"])
-@pytest.mark.parametrize("tuning", [None, (128, 16), (128, 8), (96, 16), (128, 112), (128, 108), (96, 112), (64, 102), (32, 101), (16, 101), (16, 103), (32, 103),
+@pytest.mark.parametrize("tuning", [None, (128, 16), (128, 8), (96, 16), (128, 112), (128, 108), (96, 112), (64, 112), (64, 102), (32, 101), (16, 101), (16, 103), (32, 103),
                                     (64, 104), (32, 104), (16, 104)],
-                         ids=["default", "tile128", "tile128w8", "tile96", "fed12", "fed8", "fed12tile96", "simple", "simple32", "simple16", "slab", "slab32",
+                         ids=["default", "tile128", "tile128w8", "tile96", "fed12", "fed8", "fed12tile96", "fed12tile64", "simple", "simple32", "simple16", "slab", "slab32",
                               "stream64", "stream32", "stream16"])
 def test_ragged_shapes(N, K, M, out_type, tuning):
     case = wl.Case("ragged", N, K, M, 0.6, wl.N4K1, out_type, "none", keys=(60, N, K, M))
@@ -377,7 +377,7 @@ def test_many_token_tiles_and_segments(N, K, M, s):
     """Several token tiles per workgroup stream, 1 / 2 / 3+ K segments (resident and
     re-streamed weights), ragged last tile, every step-count variant of the kernel."""
     for ot, po in (("s32", "none"), ("s8", "gelu")):
-        for tuning in (None, (128, 0), (128, 8), (96, 0), (128, 112), (128, 108), (96, 112)):
+        for tuning in (None, (128, 0), (128, 8), (96, 0), (128, 112), (128, 108), (96, 112), (64, 112)):
             check_case(wl.Case("multi", N, K, M, s, wl.N4K1, ot, po, keys=(66, N, K, M)), tuning=tuning)
     # 4-byte outputs: the plan's own choice there is a workgroup with loader waves
     for ot, po in (("f32", "none"), ("f32", "gelu")):

@@ -284,8 +284,10 @@ def test_plan_picks_token_tile_and_waves_per_shape():
 
     assert kernel32(3072, 768, 4096) == ("void spmm::spmm_rowtile_mfma_fed<128, 12, 4, 4, 1, 0>(spmm::KernelArgs)",
                                          (128, 192, 256))           # 16 row groups x 16 streams of 2 tiles
-    assert kernel32(768, 3072, 4096)[0] == "void spmm::spmm_rowtile_mfma_fed<128, 8, 4, 4, 1, 0>(spmm::KernelArgs)"
-    assert kernel32(768, 768, 4096, "s32")[0] == "void spmm::spmm_rowtile_mfma_fed<128, 8, 4, 4, 0, 0>(spmm::KernelArgs)"
+    assert kernel32(768, 3072, 4096)[0] == "void spmm::spmm_rowtile_mfma_fed<64, 12, 4, 4, 1, 0>(spmm::KernelArgs)"
+    assert kernel32(768, 768, 4096, "s32")[0] == "void spmm::spmm_rowtile_mfma_fed<64, 12, 4, 4, 0, 0>(spmm::KernelArgs)"
+    assert kernel32(1024, 1024, 4096)[0] == "void spmm::spmm_rowtile_mfma_fed<128, 8, 4, 4, 1, 0>(spmm::KernelArgs)"
+    assert kernel32(768, 3072, 6144)[0] == "void spmm::spmm_rowtile_mfma_fed<96, 12, 4, 4, 1, 0>(spmm::KernelArgs)"
     assert kernel32(768, 768, 128)[0].startswith("void spmm::spmm_rowtile_mfma_simple<16")    # short batches: unchanged
     assert kernel32(1024, 1024, 6144, "f32", (96, 112))[0] == "void spmm::spmm_rowtile_mfma_fed<96, 12, 4, 4, 1, 0>(spmm::KernelArgs)"
     assert kernel32(1024, 1024, 6144, "f32", (128, 108))[1] == (128, 128, 256)
