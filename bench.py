@@ -197,6 +197,7 @@ def main() -> int:
     ap.add_argument("--reorder", action="store_true",
                     help="pack with SPMM_PACK_REORDER_ROWS (rows clustered by k overlap); outputs and per-row "
                          "operands are then in the library's row order")
+    ap.add_argument("--no-tile-major", action="store_true", help="skip the extra timing with token-tile-major activations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--tuning", default="", help="token_tile,variant override passed to spmm_set_tuning")
@@ -415,6 +416,57 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         b2b_us.append(e0.elapsed_time(e1) * 1e3 / args.steps)
+    # ------------------------------------------------------------------ extra: the same steps with the activations
+    # handed over in token-tile-major order (spmm_run_tiled), eager back to back and with events per launch
+    tile_major = None
+    if not args.profile and all(c["d"]["X"] is not None for c in calls) and not args.no_tile_major:
+        for c in calls:
+            xt = sp.tile_major(c["d"]["X"])
+            c["Xt"] = [torch.from_numpy(xt).cuda() for _ in range(ROTATE)]
+            c["run_t"] = [sp.spmm_run_tiled_bound(c["h"], c["Xt"][j], c["M"], c["eps"][j], c["outs"][j], c["M"], stream)
+                          for j in range(ROTATE)]
+        # (results first: bit-identical to the row-major launch of the same call)
+        same = True
+        for c in calls:
+            launch(c, 0)
+            torch.cuda.synchronize()
+            ref_out = c["outs"][0].clone()
+            c["outs"][0].zero_()
+            c["run_t"][0]()
+            torch.cuda.synchronize()
+            same &= bool(torch.equal(ref_out.view(torch.uint8), c["outs"][0].view(torch.uint8)))
+        for it in range(max(2, args.warmup // 2)):
+            for c in calls:
+                c["run_t"][it % ROTATE]()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for it in range(args.steps):
+            for c in calls:
+                c["run_t"][it % ROTATE]()
+        e1.record()
+        torch.cuda.synchronize()
+        t_ms = e0.elapsed_time(e1) / args.steps
+        evt = [[torch.cuda.Event(enable_timing=True) for _ in range(nc + 1)] for _ in range(args.steps)]
+        for it in range(args.steps):
+            evt[it][0].record()
+            for ci, c in enumerate(calls):
+                c["run_t"][it % ROTATE]()
+                evt[it][ci + 1].record()
+        torch.cuda.synchronize()
+        t_ev_ms = evt[0][0].elapsed_time(evt[args.steps - 1][nc]) / args.steps
+        t_call = np.array([[evt[it][ci].elapsed_time(evt[it][ci + 1]) * 1e3 for ci in range(nc)]
+                           for it in range(args.steps)]).mean(axis=0) * (t_ms / t_ev_ms)
+        tile_major = {"layout": "X as [ceil(M/32)][K][32] (spmm_run_tiled), outputs row-major",
+                      "ms_per_step": round(t_ms, 5),
+                      "value": round(sum(c["dense_ops"] for c in calls) / (t_ms * 1e-3) / 1e12, 2),
+                      "same_bits_as_row_major": same,
+                      "per_call_us_in_step": {c["case"].name: round(float(t_call[i]), 2) for i, c in enumerate(calls)},
+                      "per_call_roofline_frac_in_step": {c["case"].name: round(c["bytes"] / (float(t_call[i]) * 1e-6) / (HBM_PEAK_GBS * 1e9), 4)
+                                                         for i, c in enumerate(calls)}}
+        for c in calls:
+            del c["Xt"], c["run_t"]
+
     # `value` and the roofline use ONE launch mode: plain eager launches back to back on the stream (what a
     # caller of spmm_run gets; graph replay of the same steps is reported beside it)
     ms_per_step, launch_mode = stream_ms_per_step, "eager_back_to_back"
@@ -625,6 +677,7 @@ def main() -> int:
         "nonzero_tops": round(nnz_tops, 2),
         "roofline": roofline, "cpu_baseline": cpu, "dense_int8_gemm": dense, "qkv_stacked": qkv, "per_call": rows,
         "base_f32": base_f32,
+        "tile_major_x": tile_major,
         "ms_per_step_eager_with_events": round(eager_ms_per_step, 5),
         "ms_per_step_graph": (round(graph_ms_per_step, 5) if graph_ms_per_step is not None else None),
         "ms_per_step_eager_back_to_back": round(stream_ms_per_step, 5),

@@ -179,6 +179,18 @@ spmm_status_t spmm_layout_export(const spmm_handle_t *h, uint8_t *vals_host, uin
 spmm_status_t spmm_run(const spmm_handle_t *h, const uint8_t *X_dev, int64_t M, int64_t ldx,
                        const spmm_epilogue_t *ep, void *out_dev, int64_t ldo, void *hip_stream);
 
+/* spmm_run with the activations in TOKEN-TILE-MAJOR order (Section 3.2 re-structures the input for
+ * the kernel's blocking; this is that layout for this kernel): X_tiled_dev is
+ *     uint8 [ceil(M / SPMM_X_TILE)][K][SPMM_X_TILE],   X_tiled[t][k][j] = X[k][SPMM_X_TILE * t + j],
+ * device memory, 16-byte aligned, the last tile padded to full width (the padding is read and never
+ * used).  A workgroup's token tile is then three or four contiguous regions of memory instead of K
+ * pieces a row pitch apart, which is what HBM wants when X does not come out of a cache.  Everything else
+ * (M, epilogue, output, stream, errors) as in spmm_run; the whole X must be smaller than 2 GiB
+ * (SPMM_E_UNSUPPORTED otherwise). */
+#define SPMM_X_TILE 32
+spmm_status_t spmm_run_tiled(const spmm_handle_t *h, const uint8_t *X_tiled_dev, int64_t M,
+                             const spmm_epilogue_t *ep, void *out_dev, int64_t ldo, void *hip_stream);
+
 /* Algorithm 2: the 256-entry table of the chain dequantise(mid_scale) -> GELU ->
  * quantise(out_scale, out_zero_point), entry [i + 128] for key i in [-128, 127], computed
  * in double and rounded half to even.  lut_host is HOST memory; the caller copies it to

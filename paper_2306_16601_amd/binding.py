@@ -28,7 +28,7 @@ OUT_TYPES = {"s32": SPMM_OUT_S32, "f32": SPMM_OUT_F32, "s8": SPMM_OUT_S8, "u8": 
 
 EXPORTS = (
     "spmm_pack", "spmm_pack_host", "spmm_pack_ex", "spmm_row_order", "spmm_unpack", "spmm_info", "spmm_layout_dims",
-    "spmm_layout_export", "spmm_run", "spmm_make_gelu_lut", "spmm_plan", "spmm_set_tuning",
+    "spmm_layout_export", "spmm_run", "spmm_run_tiled", "spmm_make_gelu_lut", "spmm_plan", "spmm_set_tuning",
     "spmm_kernel_name", "spmm_kernel_variant", "spmm_measure_peak", "spmm_destroy", "spmm_status_string",
 )
 
@@ -87,6 +87,8 @@ def lib() -> ctypes.CDLL:
         L.spmm_layout_export.argtypes = [vp, vp, vp, vp, vp]
         L.spmm_run.restype = ci
         L.spmm_run.argtypes = [vp, vp, i64, i64, P(spmm_epilogue_t), vp, i64, vp]
+        L.spmm_run_tiled.restype = ci
+        L.spmm_run_tiled.argtypes = [vp, vp, i64, P(spmm_epilogue_t), vp, i64, vp]
         L.spmm_make_gelu_lut.restype = ci
         L.spmm_make_gelu_lut.argtypes = [f32, f32, i32, ci, vp]
         L.spmm_plan.restype = ci
@@ -272,6 +274,39 @@ def spmm_run_status(handle: int, X_dev, M: int, ldx: int, ep: Optional[spmm_epil
 def spmm_run(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, out_dev, ldo: int, stream=None) -> None:
     """out = postops(W . X), asynchronous on `stream` (a raw hipStream_t value, None = default stream)."""
     _check(spmm_run_status(handle, X_dev, M, ldx, ep, out_dev, ldo, stream), "spmm_run")
+
+
+SPMM_X_TILE = 32
+
+
+def tile_major(X: np.ndarray) -> np.ndarray:
+    """Host helper: uint8 [K, M] row-major -> the token-tile-major order spmm_run_tiled reads,
+    [ceil(M / 32), K, 32], last tile zero-padded (data movement only)."""
+    K, M = X.shape
+    T = (M + SPMM_X_TILE - 1) // SPMM_X_TILE
+    Xp = np.zeros((K, T * SPMM_X_TILE), dtype=X.dtype)
+    Xp[:, :M] = X
+    return np.ascontiguousarray(Xp.reshape(K, T, SPMM_X_TILE).transpose(1, 0, 2))
+
+
+def spmm_run_tiled(handle: int, X_tiled_dev, M: int, ep: spmm_epilogue_t, out_dev, ldo: int, stream=None) -> None:
+    """spmm_run with the activations in token-tile-major order (see tile_major)."""
+    st = None if stream is None else int(stream)
+    _check(int(lib().spmm_run_tiled(handle, _dev_ptr(X_tiled_dev), int(M), ctypes.byref(ep), _dev_ptr(out_dev),
+                                    int(ldo), st)), "spmm_run_tiled")
+
+
+def spmm_run_tiled_bound(handle: int, X_tiled_dev, M: int, ep: spmm_epilogue_t, out_dev, ldo: int, stream=None):
+    """spmm_run_tiled with its arguments marshalled once (see spmm_run_bound)."""
+    fn = lib().spmm_run_tiled
+    args = (ctypes.c_void_p(handle), ctypes.c_void_p(_dev_ptr(X_tiled_dev)), ctypes.c_int64(int(M)), ctypes.byref(ep),
+            ctypes.c_void_p(_dev_ptr(out_dev)), ctypes.c_int64(int(ldo)),
+            ctypes.c_void_p(None if stream is None else int(stream)))
+
+    def call() -> int:
+        return fn(*args)
+    call._keepalive = (ep, X_tiled_dev, out_dev)
+    return call
 
 
 def spmm_run_bound(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, out_dev, ldo: int, stream=None):

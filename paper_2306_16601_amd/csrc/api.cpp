@@ -211,8 +211,23 @@ spmm_status_t spmm_set_tuning(spmm_handle_t* h, int32_t token_tile, int32_t vari
     return SPMM_OK;
 }
 
+static spmm_status_t run_common(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, int64_t ldx, bool x_tiled,
+                                const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, void* hip_stream);
+
 spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, int64_t ldx,
                        const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, void* hip_stream)
+{
+    return run_common(h, X_dev, M, ldx, false, ep, out_dev, ldo, hip_stream);
+}
+
+spmm_status_t spmm_run_tiled(const spmm_handle_t* h, const uint8_t* X_tiled_dev, int64_t M,
+                             const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, void* hip_stream)
+{
+    return run_common(h, X_tiled_dev, M, M, true, ep, out_dev, ldo, hip_stream);
+}
+
+static spmm_status_t run_common(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, int64_t ldx, bool x_tiled,
+                                const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, void* hip_stream)
 {
     if (!h || !X_dev || !ep || !out_dev) return SPMM_E_ARG;
     if (!h->on_device) return SPMM_E_ARG;   // packed with spmm_pack_host: nothing to run on
@@ -262,6 +277,15 @@ spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, 
     a.x_scale = ep->x_scale;
     // fast paths use 16-byte accesses and 32-bit offsets
     a.x_vec_ok = aligned(X_dev, 16) && (ldx % 16 == 0) && (h->bsr.K * ldx < ((int64_t)1 << 31));
+    if (x_tiled) {
+        // token-tile-major activations: [ceil(M / 32)][K][32] bytes, 16-byte aligned
+        if (!aligned(X_dev, 16)) return SPMM_E_ARG;
+        const int64_t tiles = (M + SPMM_X_TILE - 1) / SPMM_X_TILE;
+        if (tiles * h->bsr.K * SPMM_X_TILE >= ((int64_t)1 << 31)) return SPMM_E_UNSUPPORTED;
+        a.ldx = SPMM_X_TILE;
+        a.x_tile_stride = (int)(h->bsr.K * SPMM_X_TILE);
+        a.x_vec_ok = 1;
+    }
     const int64_t esz = quant ? 1 : 4;
     a.out_vec_ok = aligned(out_dev, 16) && ((ldo * esz) % 16 == 0) && (h->bsr.N * ldo * esz < ((int64_t)1 << 31));
     if (ep->sum) {

@@ -85,9 +85,10 @@ struct KernelArgs {
     int xcd_map;         // simple / short-batch kernels: how a workgroup id decodes, see decode_workgroup()
     int corr_mul;        // 128 - x_zero_point: the activations are multiplied as (x - 128)
     float x_scale, inv_out, inv_mid, out_zp_f;
-    int x_vec_ok;        // X base 16-byte aligned, ldx % 16 == 0 and K * ldx < 2^31
+    int x_vec_ok;        // X base 16-byte aligned, ldx % 16 == 0 and K * ldx < 2^31 (tile-major: the whole X < 2^31 bytes)
     int out_vec_ok;      // out base 16-byte aligned, row pitch a multiple of 16 bytes, whole output < 2^31 bytes
                          // (and, with Sum, the same for the second operand)
+    int x_tile_stride;   // 0: X row-major [K][ldx]; else X token-tile-major [ceil(M/32)][K][32], ldx = 32 and this = 32 K
 };
 
 struct Plan {

@@ -188,15 +188,34 @@ __device__ __forceinline__ v4i piece_mask(const int nv)
     return m;
 }
 
+// Byte offset of token column `col` inside an activation row.  Row-major X: the column itself (rows
+// are ldx apart).  Token-tile-major X, [ceil(M / 32)][K][32] (the re-structured input of Section 3.2:
+// the rows of a 32-token tile lie back to back, so a workgroup's token tile is three or four
+// contiguous regions of memory): rows are 32 bytes apart and a column's tile starts
+// x_tile_stride = 32 K bytes after the previous one.  16-byte pieces start at multiples of 16 and
+// never straddle two tiles; xcol(c1 + c2) = xcol(c1) + xcol(c2) when c1 is a multiple of 32.
+// XT: 1 = token-tile-major, 0 = row-major, -1 = whichever the arguments say (a uniform run-time test).
+// The pipelined kernel is instantiated for both layouts: its 16-wave forms have no register to spare
+// for a choice at run time.
+template <int XT = -1>
+__device__ __forceinline__ int xcol(const KernelArgs& a, const int col)
+{
+    // (the whole X is smaller than 2 GiB in this layout, checked on the host: the offset fits an int)
+    if constexpr (XT == 0) return col;
+    else if constexpr (XT == 1) return (col >> 5) * a.x_tile_stride + (col & 31);
+    else return a.x_tile_stride ? (col >> 5) * a.x_tile_stride + (col & 31) : col;
+}
+
 // 16 bytes of activation row `krow` starting at token `col`; tokens >= M read as 0.
 // The general path (odd leading dimension or base, or the last, partial piece of a row) reads the
 // aligned dwords that hold the wanted bytes and shifts them into place: every dword read holds
 // at least one wanted byte, so nothing outside the pages of X is touched, and a piece costs at
 // most five loads (byte loads of 64 different rows cost a cache-line look-up each: a 13-token
 // tail made the whole launch three times longer).
+template <int XT = -1>
 __device__ __forceinline__ v4i load_x16(const KernelArgs& a, const int krow, const int col)
 {
-    const uint8_t* src = a.X + (int64_t)krow * a.ldx + col;
+    const uint8_t* src = a.X + (int64_t)krow * a.ldx + xcol<XT>(a, col);
     const int nbytes = min(16, a.M - col);
     if (a.x_vec_ok && nbytes == 16) return *(const v4i*)src;
     v4i v = {0, 0, 0, 0};
@@ -220,9 +239,10 @@ __device__ __forceinline__ v4i load_x16(const KernelArgs& a, const int krow, con
 
 // The same, byte by byte: few registers (the 16-wave pipelined kernels have 128 and none to
 // spare for a path they take only with unaligned activations), slow.
+template <int XT = -1>
 __device__ __forceinline__ v4i load_x16_bytewise(const KernelArgs& a, const int krow, const int col)
 {
-    const uint8_t* src = a.X + (int64_t)krow * a.ldx + col;
+    const uint8_t* src = a.X + (int64_t)krow * a.ldx + xcol<XT>(a, col);
     if (a.x_vec_ok && col + 16 <= a.M) return *(const v4i*)src;
     v4i v = {0, 0, 0, 0};
 #pragma unroll
@@ -378,7 +398,7 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
     }
 }
 
-template <int TM, int NW, int MAXS, int OUT, int POST>
+template <int TM, int NW, int MAXS, int OUT, int POST, int XT = 0>
 __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
 {
     using G = Geo<TM>;
@@ -448,38 +468,57 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         const int k0 = seg * SEGMENT_ROWS;
         const int last = min(SEGMENT_ROWS, a.K - k0) - 1;
         if (!stager) return;
-        if (a.x_vec_ok && tok0 + TM <= a.M) {
-            // fast path: K * ldx < 2 GiB (checked on the host), 32-bit offsets from a uniform base
-            const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0;
+        if constexpr (XT == 0) {
+            if (a.x_vec_ok && tok0 + TM <= a.M) {
+                // fast path: K * ldx < 2 GiB (checked on the host), 32-bit offsets from a uniform base
+                const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0;
 #pragma unroll
-            for (int u = 0; u < XH; ++u) {
-                const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
-                xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(x_piece * 16)));
-            }
-        } else if (a.x_vec_ok && (MASKED_TAIL || (a.M & 15) == 0)) {
-            // ragged last tile of an aligned matrix: a piece is whole, beyond the end, or cut by it.
-            // The cut one is read whole as well (an aligned 16-byte chunk that holds a wanted byte
-            // lies inside the row pitch) and masked: branch-free.  (Without MASKED_TAIL only token
-            // counts that are multiples of 16 come here: no piece is cut.)
-            const uint8_t* src = a.X + (int64_t)k0 * a.ldx;
-            const int col = tok0 + x_piece * 16;
-            const bool in = col < a.M;
+                for (int u = 0; u < XH; ++u) {
+                    const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
+                    xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(x_piece * 16)));
+                }
+            } else if (a.x_vec_ok && (MASKED_TAIL || (a.M & 15) == 0)) {
+                // ragged last tile of an aligned matrix: a piece is whole, beyond the end, or cut by it.
+                // The cut one is read whole as well (an aligned 16-byte chunk that holds a wanted byte
+                // lies inside the row pitch) and masked: branch-free.  (Without MASKED_TAIL only token
+                // counts that are multiples of 16 come here: no piece is cut.)
+                const uint8_t* src = a.X + (int64_t)k0 * a.ldx;
+                const int col = tok0 + x_piece * 16;
+                const bool in = col < a.M;
 #pragma unroll
-            for (int u = 0; u < XH; ++u) {
-                const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
-                const v4i v = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(in ? col : 0)));
-                if constexpr (MASKED_TAIL) xr[u] = v & piece_mask(a.M - col);
-                else xr[u] = in ? v : (v4i){0, 0, 0, 0};
+                for (int u = 0; u < XH; ++u) {
+                    const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
+                    const v4i v = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(in ? col : 0)));
+                    if constexpr (MASKED_TAIL) xr[u] = v & piece_mask(a.M - col);
+                    else xr[u] = in ? v : (v4i){0, 0, 0, 0};
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < XH; ++u) {
+                    const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
+                    if constexpr (NW == 16) xr[u] = load_x16_bytewise<0>(a, k0 + row, tok0 + x_piece * 16);
+                    else xr[u] = load_x16<0>(a, k0 + row, tok0 + x_piece * 16);
+                }
             }
         } else {
+            // token-tile-major activations: the layout is 16-byte aligned and padded to whole 32-token tiles, so
+            // a piece that starts before M is read whole and one that starts at or after M is not needed at
+            // all (its columns are never stored): one branch-free form, no masks, no unaligned path
+            // (the piece's offset is worked out again at every call, from a thread id the compiler cannot
+            // see through: kept in a register across the phases it would be one register too many)
+            int t = tid;
+            asm volatile("" : "+v"(t));
+            const int col = tok0 + (t % PIECES) * 16;
+            const uint8_t* src = a.X + (int64_t)k0 * 32;
+            const uint32_t off = col < a.M ? (uint32_t)xcol<1>(a, col) : 0u;
 #pragma unroll
             for (int u = 0; u < XH; ++u) {
                 const int row = min(x_row0 + (h * XH + u) * ROWS_PER_PASS, last);
-                if constexpr (NW == 16) xr[u] = load_x16_bytewise(a, k0 + row, tok0 + x_piece * 16);
-                else xr[u] = load_x16(a, k0 + row, tok0 + x_piece * 16);
+                xr[u] = *(const v4i*)(src + ((uint32_t)row * 32u + off));
             }
         }
     };
+
     // ---- ... and from registers into LDS buffer q % 2, as x - 128
     auto x_commit_from = [&](const v4i (&xr)[XH], const int q, const int h) {
         if (!stager) return;
@@ -674,6 +713,7 @@ __global__ void __launch_bounds__((NW + LW) * 64) spmm_rowtile_mfma_fed(const Ke
         const bool stager = ltid < STAGERS;
         const int x_row0 = ltid / PIECES, x_piece = ltid % PIECES;
         const uint32_t x_lds0 = G::X0 + (uint32_t)x_row0 * G::STRIDE + x_piece * 16;
+        const uint32_t x_off = (uint32_t)xcol(a, x_piece * 16);
         v4i xr[XLOADS];
         auto x_issue = [&](const int q) {
             const int j = q / a.nseg, seg = q - j * a.nseg;
@@ -682,11 +722,11 @@ __global__ void __launch_bounds__((NW + LW) * 64) spmm_rowtile_mfma_fed(const Ke
             const int last = min(SEGMENT_ROWS, a.K - k0) - 1;   // rows past K repeat the last one (never multiplied)
             if (!stager) return;
             if (a.x_vec_ok && tok0 + TM <= a.M) {
-                const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0;
+                const uint8_t* src = a.X + (int64_t)k0 * a.ldx + xcol(a, tok0);
 #pragma unroll
                 for (int u = 0; u < XLOADS; ++u) {
                     const int row = min(x_row0 + u * ROWS_PER_PASS, last);
-                    xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(x_piece * 16)));
+                    xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + x_off));
                 }
             } else if (a.x_vec_ok) {
                 // ragged last tile of an aligned matrix: a piece is whole, beyond the end, or cut by it;
@@ -698,7 +738,7 @@ __global__ void __launch_bounds__((NW + LW) * 64) spmm_rowtile_mfma_fed(const Ke
 #pragma unroll
                 for (int u = 0; u < XLOADS; ++u) {
                     const int row = min(x_row0 + u * ROWS_PER_PASS, last);
-                    xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(in ? col : 0))) & mask;
+                    xr[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)xcol(a, in ? col : 0))) & mask;
                 }
             } else {
 #pragma unroll
@@ -888,12 +928,12 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
         const int k0 = seg * SEGMENT_ROWS;
         const int last = min(SEGMENT_ROWS, a.K - k0) - 1;      // rows past K repeat the last one (never multiplied)
         if (a.x_vec_ok && tok0 + TM <= a.M) {
-            const uint8_t* src = a.X + (int64_t)k0 * a.ldx + tok0;
+            const uint8_t* src = a.X + (int64_t)k0 * a.ldx;
 #pragma unroll
             for (int u = 0; u < XL; ++u) {
                 const int p = tid + u * NW * 64;
                 const int row = min(p / PIECES, last), piece = p % PIECES;
-                xs[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(piece * 16)));
+                xs[u] = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)xcol(a, tok0 + piece * 16)));
             }
         } else if (a.x_vec_ok) {
             // ragged last tile of an aligned matrix: whole pieces, none, or the cut one read whole
@@ -904,7 +944,7 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_simple(const Kernel
                 const int p = tid + u * NW * 64;
                 const int row = min(p / PIECES, last), col = tok0 + (p % PIECES) * 16;
                 const bool in = col < a.M;
-                const v4i v = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(in ? col : 0)));
+                const v4i v = *(const v4i*)(src + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)xcol(a, in ? col : 0)));
                 xs[u] = v & piece_mask(a.M - col);
             }
         } else {
@@ -1024,9 +1064,9 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_slab(const KernelAr
                 const int p = tid + u * NW * 64;
                 const int row = min(seg * SEGMENT_ROWS + p / PIECES, a.K - 1), col = tok0 + (p % PIECES) * 16;
                 if (fast) {
-                    xr[seg][u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)col));
+                    xr[seg][u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)xcol(a, col)));
                 } else if (a.x_vec_ok) {      // ragged last tile of an aligned matrix: whole chunks, masked
-                    const v4i v = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(col < a.M ? col : 0)));
+                    const v4i v = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)xcol(a, col < a.M ? col : 0)));
                     xr[seg][u] = v & piece_mask(a.M - col);
                 } else {
                     xr[seg][u] = load_x16(a, row, col);
@@ -1176,9 +1216,9 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma_stream(const Kernel
             const int p = tid + u * NW * 64;
             const int row = k0 + min(p / PIECES, last), col = tok0 + (p % PIECES) * 16;
             if (fast) {
-                xs[u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)col));
+                xs[u] = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)xcol(a, col)));
             } else if (a.x_vec_ok) {          // ragged last tile of an aligned matrix: whole chunks, masked
-                const v4i v = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)(col < a.M ? col : 0)));
+                const v4i v = *(const v4i*)(a.X + ((uint32_t)row * (uint32_t)a.ldx + (uint32_t)xcol(a, col < a.M ? col : 0)));
                 xs[u] = v & piece_mask(a.M - col);
             } else {
                 xs[u] = load_x16(a, row, col);

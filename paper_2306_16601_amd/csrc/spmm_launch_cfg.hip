@@ -131,7 +131,9 @@ struct PipeLaunch {
     template <int OUT, int POST>
     static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
     {
-        hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST>), grid, block, 0, st, a);
+        // one instantiation per activation layout (row-major / token-tile-major)
+        if (a.x_tile_stride) hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST, 1>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST, 0>), grid, block, 0, st, a);
     }
 };
 }  // namespace

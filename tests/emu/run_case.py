@@ -2,7 +2,7 @@
 Called as a subprocess by tests/test_emulated_kernels.py (a kernel that reads or writes outside
 its buffers ends this process with a segmentation fault, a barrier that not every wave reaches
 ends it with the emulator's deadlock report): prints one JSON line.
-usage: python run_case.py N K M sparsity out_type postop token_tile variant ldx ldo cus [weight kind]"""
+usage: python run_case.py N K M sparsity out_type postop token_tile variant ldx ldo cus [weight kind [xtiled]]"""
 import ctypes
 import json
 import os
@@ -21,6 +21,7 @@ def main():
     sparsity, ot, po = float(sys.argv[4]), sys.argv[5], sys.argv[6]
     tm, var, ldx, ldo, cus = (int(v) for v in sys.argv[7:12])
     kind = sys.argv[12] if len(sys.argv) > 12 else "uniform"
+    x_tiled = len(sys.argv) > 13 and sys.argv[13] == "xtiled"
     os.environ["EMU_CUS"] = str(cus)
     import build_emu
     import paper_2306_16601_amd.binding as b
@@ -64,7 +65,14 @@ def main():
     nbytes = N * ldo * np.dtype(dt).itemsize
     od = L.emu_alloc(nbytes)
     ctypes.memset(od, 0x5A, nbytes)
-    sp.spmm_run(h, dev(Xp), M, ldx, ep, od, ldo, None)
+    if x_tiled:
+        # token-tile-major activations in an allocation of exactly their size (guard pages behind it);
+        # the padding of the last tile is poisoned
+        Xt = sp.tile_major(X)
+        Xt[-1, :, M - 32 * (Xt.shape[0] - 1):] = 0xEE
+        sp.spmm_run_tiled(h, dev(Xt), M, ep, od, ldo, None)
+    else:
+        sp.spmm_run(h, dev(Xp), M, ldx, ep, od, ldo, None)
     full = np.empty((N, ldo), dtype=dt)
     ctypes.memmove(full.ctypes.data, od, nbytes)
     got = full[:, :M]

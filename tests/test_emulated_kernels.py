@@ -32,9 +32,9 @@ def emu_lib():
     return build_emu.build()
 
 
-def run_case(N, K, M, sparsity, out_type, postop, tm, variant, ldx=0, ldo=0, cus=4, kind="uniform"):
+def run_case(N, K, M, sparsity, out_type, postop, tm, variant, ldx=0, ldo=0, cus=4, kind="uniform", xtiled=False):
     cmd = [sys.executable, os.path.join(HERE, "emu", "run_case.py"), str(N), str(K), str(M), str(sparsity), out_type,
-           postop, str(tm), str(variant), str(ldx), str(ldo), str(cus), kind]
+           postop, str(tm), str(variant), str(ldx), str(ldo), str(cus), kind] + (["xtiled"] if xtiled else [])
     r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, "emulated kernel run failed (rc %d):\n%s" % (r.returncode, r.stderr[-3000:])
     return json.loads(r.stdout.strip().splitlines()[-1])
@@ -56,6 +56,12 @@ CASES = [
     (272, 700, 250, 0.8, "f32", "gelu", 128, 112, "spmm_rowtile_mfma_fed<128, 8", {"cus": 2, "ldx": 251, "ldo": 253, "kind": "ragged"}),
     (272, 700, 250, 0.8, "s8", "gelu", 64, 112, "spmm_rowtile_mfma_fed<128, 8", {"cus": 2, "kind": "ragged"}),   # dense tile: falls back to 8 + 4
     (200, 600, 203, 0.9, "u8", "none", 64, 112, "spmm_rowtile_mfma_fed<64, 12", {"cus": 2, "ldx": 211, "ldo": 209}),
+    # token-tile-major activations ([M / 32][K][32], exactly sized allocation): one case per kernel family
+    (300, 1000, 333, 0.85, "s8", "gelu", 96, 16, "spmm_rowtile_mfma<96, 16", {"cus": 2, "xtiled": True}),
+    (256, 1536, 200, 0.9, "s32", "none", 128, 112, "spmm_rowtile_mfma_fed<128, 12", {"cus": 2, "xtiled": True}),
+    (128, 700, 150, 0.8, "s8", "none", 64, 101, "spmm_rowtile_mfma_simple<64", {"xtiled": True}),
+    (128, 2560, 40, 0.9, "s32", "none", 16, 103, "spmm_rowtile_mfma_slab<16", {"xtiled": True}),
+    (128, 3584, 70, 0.9, "s8", "gelu", 32, 104, "spmm_rowtile_mfma_stream<32", {"xtiled": True}),
     # simple kernel at its three tile widths
     (256, 1024, 192, 0.9, "s8", "gelu", 64, 101, "spmm_rowtile_mfma_simple<64", {}),
     (512, 768, 128, 0.8, "s32", "none", 64, 102, "spmm_rowtile_mfma_simple<64", {}),

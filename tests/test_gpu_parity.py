@@ -22,8 +22,9 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def gpu_spmm(W, X, d, case, ldx=None, ldo=None, tuning=None, stream=None, x_offset=0, out_offset=0):
-    """Pack W, run the library on device copies of the inputs, return (out, guards_ok)."""
+def gpu_spmm(W, X, d, case, ldx=None, ldo=None, tuning=None, stream=None, x_offset=0, out_offset=0, x_tiled=False):
+    """Pack W, run the library on device copies of the inputs, return (out, guards_ok).
+    x_tiled: hand the activations over in token-tile-major order (spmm_run_tiled)."""
     N, K = W.shape
     M = X.shape[1]
     ldx = ldx or M
@@ -49,7 +50,12 @@ def gpu_spmm(W, X, d, case, ldx=None, ldo=None, tuning=None, stream=None, x_offs
         ep = sp.make_epilogue(w_scale, d["x_scale"], d["x_zero_point"], bias, case.postop, ot,
                               d["out_scale"], d["out_zero_point"], d["mid_scale"], lut)
         st = stream.cuda_stream if stream is not None else torch.cuda.current_stream().cuda_stream
-        sp.spmm_run(h, Xv, M, ldx, ep, oview, ldo, st)
+        if x_tiled:
+            Xt = dev(sp.tile_major(X))
+            Xt[-1, :, M - sp.binding.SPMM_X_TILE * (Xt.shape[0] - 1):] = 0xEE      # the padding of the last tile must never matter
+            sp.spmm_run_tiled(h, Xt, M, ep, oview, ldo, st)
+        else:
+            sp.spmm_run(h, Xv, M, ldx, ep, oview, ldo, st)
         torch.cuda.synchronize()
         out = oview[:, :M].cpu().numpy()
         full = obuf.cpu().numpy()
@@ -612,5 +618,33 @@ def test_reordered_rows_are_the_oracles_rows_in_the_reported_order(orient, N, K,
         sp.spmm_run(h, dev(d["X"]), M, M, ep, out, M, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         assert_parity(out.cpu().numpy(), np.ascontiguousarray(ref[order]), case)
+    finally:
+        sp.spmm_destroy(h)
+
+
+# ------------------------------------------------ token-tile-major activations (Section 3.2: re-structured input)
+@pytest.mark.parametrize("tuning", [None, (128, 16), (128, 8), (96, 16), (128, 112), (128, 108), (96, 112), (64, 112), (64, 101),
+                                    (64, 102), (32, 101), (16, 101), (16, 103), (32, 103), (64, 104), (32, 104), (16, 104)],
+                         ids=lambda t: "auto" if t is None else "%d_%d" % t)
+@pytest.mark.parametrize("N,K,M,s,out_type,postop", [(272, 1100, 700, 0.9, "s8", "gelu"), (100, 600, 333, 0.8, "s32", "none"),
+                                                      (512, 2048, 1280, 0.9, "f32", "none"), (64, 520, 50, 0.7, "u8", "none")])
+def test_tile_major_activations(N, K, M, s, out_type, postop, tuning):
+    """spmm_run_tiled reads X as [ceil(M / 32)][K][32]: same results as the oracle on the row-major X,
+    in every kernel family, with ragged token counts (the padding of the last tile is poisoned)."""
+    case = wl.Case("xtiled", N, K, M, s, wl.N4K1, out_type, postop, keys=(83, N, K, M))
+    check_case(case, tuning=tuning, x_tiled=True)
+
+
+def test_tile_major_large_case_and_argument_errors():
+    case = wl.large_cases()[4]                                   # 1024 x 4096, 6144 tokens: eight K segments, 96-token tiles
+    check_case(case, x_tiled=True)
+    d = wl.make(wl.tiny_cases()[0])
+    h = sp.spmm_pack(d["W"])
+    try:
+        ep = sp.make_epilogue(None, 1.0, 0, None, "none", "s32", 1.0, 0, 1.0, None)
+        Xt = dev(sp.tile_major(d["X"]))
+        out = torch.zeros((256, 128), dtype=torch.int32, device="cuda")
+        with pytest.raises(sp.SpmmError):                        # activations must be 16-byte aligned
+            sp.spmm_run_tiled(h, Xt.view(-1)[1:], 100, ep, out, 128, None)
     finally:
         sp.spmm_destroy(h)
