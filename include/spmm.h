@@ -179,17 +179,26 @@ spmm_status_t spmm_layout_export(const spmm_handle_t *h, uint8_t *vals_host, uin
 spmm_status_t spmm_run(const spmm_handle_t *h, const uint8_t *X_dev, int64_t M, int64_t ldx,
                        const spmm_epilogue_t *ep, void *out_dev, int64_t ldo, void *hip_stream);
 
-/* spmm_run with the activations in TOKEN-TILE-MAJOR order (Section 3.2 re-structures the input for
- * the kernel's blocking; this is that layout for this kernel): X_tiled_dev is
- *     uint8 [ceil(M / SPMM_X_TILE)][K][SPMM_X_TILE],   X_tiled[t][k][j] = X[k][SPMM_X_TILE * t + j],
- * device memory, 16-byte aligned, the last tile padded to full width (the padding is read and never
- * used).  A workgroup's token tile is then three or four contiguous regions of memory instead of K
- * pieces a row pitch apart, which is what HBM wants when X does not come out of a cache.  Everything else
- * (M, epilogue, output, stream, errors) as in spmm_run; the whole X must be smaller than 2 GiB
+/* spmm_run with activations in TOKEN-TILE-MAJOR order (Section 3.2 re-structures the input for the
+ * kernel's blocking; this is that layout for this kernel).  A tile-major matrix of R rows and M tokens is
+ *     1-byte elements [ceil(M / SPMM_X_TILE)][R][SPMM_X_TILE],   T[t][r][j] = A[r][SPMM_X_TILE * t + j],
+ * device memory, 16-byte aligned, the last tile padded to full width (the padding of an input is read
+ * and never used; that of an output is not written).  A workgroup's token tile is then three or four
+ * contiguous regions of memory instead of K pieces a row pitch apart, which is what HBM wants when X
+ * does not come out of a cache.
+ *   tiled   SPMM_TILED_X    X_dev is tile-major (R = K); ldx is ignored
+ *           SPMM_TILED_OUT  the S8 / U8 output is written tile-major (R = N), i.e. as the next layer's
+ *                           tile-major activations; ldo is ignored; with S32 / F32 output:
+ *                           SPMM_E_UNSUPPORTED.  The Sum operand stays row-major.
+ *           other bits: SPMM_E_ARG.
+ * Everything else as in spmm_run; a tile-major operand must be smaller than 2 GiB
  * (SPMM_E_UNSUPPORTED otherwise). */
 #define SPMM_X_TILE 32
-spmm_status_t spmm_run_tiled(const spmm_handle_t *h, const uint8_t *X_tiled_dev, int64_t M,
-                             const spmm_epilogue_t *ep, void *out_dev, int64_t ldo, void *hip_stream);
+#define SPMM_TILED_X 1u
+#define SPMM_TILED_OUT 2u
+spmm_status_t spmm_run_tiled(const spmm_handle_t *h, const uint8_t *X_dev, int64_t M, int64_t ldx,
+                             const spmm_epilogue_t *ep, void *out_dev, int64_t ldo, uint32_t tiled,
+                             void *hip_stream);
 
 /* Algorithm 2: the 256-entry table of the chain dequantise(mid_scale) -> GELU ->
  * quantise(out_scale, out_zero_point), entry [i + 128] for key i in [-128, 127], computed

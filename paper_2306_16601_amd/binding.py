@@ -88,7 +88,7 @@ def lib() -> ctypes.CDLL:
         L.spmm_run.restype = ci
         L.spmm_run.argtypes = [vp, vp, i64, i64, P(spmm_epilogue_t), vp, i64, vp]
         L.spmm_run_tiled.restype = ci
-        L.spmm_run_tiled.argtypes = [vp, vp, i64, P(spmm_epilogue_t), vp, i64, vp]
+        L.spmm_run_tiled.argtypes = [vp, vp, i64, i64, P(spmm_epilogue_t), vp, i64, ctypes.c_uint32, vp]
         L.spmm_make_gelu_lut.restype = ci
         L.spmm_make_gelu_lut.argtypes = [f32, f32, i32, ci, vp]
         L.spmm_plan.restype = ci
@@ -280,32 +280,43 @@ SPMM_X_TILE = 32
 
 
 def tile_major(X: np.ndarray) -> np.ndarray:
-    """Host helper: uint8 [K, M] row-major -> the token-tile-major order spmm_run_tiled reads,
-    [ceil(M / 32), K, 32], last tile zero-padded (data movement only)."""
-    K, M = X.shape
+    """Host helper: 1-byte [R, M] row-major -> token-tile-major [ceil(M / 32), R, 32], last tile
+    zero-padded (data movement only)."""
+    R, M = X.shape
     T = (M + SPMM_X_TILE - 1) // SPMM_X_TILE
-    Xp = np.zeros((K, T * SPMM_X_TILE), dtype=X.dtype)
+    Xp = np.zeros((R, T * SPMM_X_TILE), dtype=X.dtype)
     Xp[:, :M] = X
-    return np.ascontiguousarray(Xp.reshape(K, T, SPMM_X_TILE).transpose(1, 0, 2))
+    return np.ascontiguousarray(Xp.reshape(R, T, SPMM_X_TILE).transpose(1, 0, 2))
 
 
-def spmm_run_tiled(handle: int, X_tiled_dev, M: int, ep: spmm_epilogue_t, out_dev, ldo: int, stream=None) -> None:
-    """spmm_run with the activations in token-tile-major order (see tile_major)."""
+def from_tile_major(T: np.ndarray, M: int) -> np.ndarray:
+    """Inverse of tile_major: [tiles, R, 32] -> row-major [R, M]."""
+    tiles, R, w = T.shape
+    return np.ascontiguousarray(T.transpose(1, 0, 2).reshape(R, tiles * w)[:, :M])
+
+
+SPMM_TILED_X, SPMM_TILED_OUT = 1, 2
+
+
+def spmm_run_tiled(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, out_dev, ldo: int, tiled: int,
+                   stream=None) -> None:
+    """spmm_run with X (SPMM_TILED_X) and / or a 1-byte output (SPMM_TILED_OUT) in token-tile-major order."""
     st = None if stream is None else int(stream)
-    _check(int(lib().spmm_run_tiled(handle, _dev_ptr(X_tiled_dev), int(M), ctypes.byref(ep), _dev_ptr(out_dev),
-                                    int(ldo), st)), "spmm_run_tiled")
+    _check(int(lib().spmm_run_tiled(handle, _dev_ptr(X_dev), int(M), int(ldx), ctypes.byref(ep), _dev_ptr(out_dev),
+                                    int(ldo), int(tiled), st)), "spmm_run_tiled")
 
 
-def spmm_run_tiled_bound(handle: int, X_tiled_dev, M: int, ep: spmm_epilogue_t, out_dev, ldo: int, stream=None):
+def spmm_run_tiled_bound(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, out_dev, ldo: int, tiled: int,
+                         stream=None):
     """spmm_run_tiled with its arguments marshalled once (see spmm_run_bound)."""
     fn = lib().spmm_run_tiled
-    args = (ctypes.c_void_p(handle), ctypes.c_void_p(_dev_ptr(X_tiled_dev)), ctypes.c_int64(int(M)), ctypes.byref(ep),
-            ctypes.c_void_p(_dev_ptr(out_dev)), ctypes.c_int64(int(ldo)),
+    args = (ctypes.c_void_p(handle), ctypes.c_void_p(_dev_ptr(X_dev)), ctypes.c_int64(int(M)), ctypes.c_int64(int(ldx)),
+            ctypes.byref(ep), ctypes.c_void_p(_dev_ptr(out_dev)), ctypes.c_int64(int(ldo)), ctypes.c_uint32(int(tiled)),
             ctypes.c_void_p(None if stream is None else int(stream)))
 
     def call() -> int:
         return fn(*args)
-    call._keepalive = (ep, X_tiled_dev, out_dev)
+    call._keepalive = (ep, X_dev, out_dev)
     return call
 
 

@@ -212,22 +212,25 @@ spmm_status_t spmm_set_tuning(spmm_handle_t* h, int32_t token_tile, int32_t vari
 }
 
 static spmm_status_t run_common(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, int64_t ldx, bool x_tiled,
-                                const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, void* hip_stream);
+                                const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, bool out_tiled, void* hip_stream);
 
 spmm_status_t spmm_run(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, int64_t ldx,
                        const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, void* hip_stream)
 {
-    return run_common(h, X_dev, M, ldx, false, ep, out_dev, ldo, hip_stream);
+    return run_common(h, X_dev, M, ldx, false, ep, out_dev, ldo, false, hip_stream);
 }
 
-spmm_status_t spmm_run_tiled(const spmm_handle_t* h, const uint8_t* X_tiled_dev, int64_t M,
-                             const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, void* hip_stream)
+spmm_status_t spmm_run_tiled(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, int64_t ldx,
+                             const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, uint32_t tiled, void* hip_stream)
 {
-    return run_common(h, X_tiled_dev, M, M, true, ep, out_dev, ldo, hip_stream);
+    if (tiled & ~(uint32_t)(SPMM_TILED_X | SPMM_TILED_OUT)) return SPMM_E_ARG;
+    const bool xt = (tiled & SPMM_TILED_X) != 0, ot = (tiled & SPMM_TILED_OUT) != 0;
+    // (a tile-major operand has no leading dimension: any value passes the range checks below)
+    return run_common(h, X_dev, M, xt ? M : ldx, xt, ep, out_dev, ot ? M : ldo, ot, hip_stream);
 }
 
 static spmm_status_t run_common(const spmm_handle_t* h, const uint8_t* X_dev, int64_t M, int64_t ldx, bool x_tiled,
-                                const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, void* hip_stream)
+                                const spmm_epilogue_t* ep, void* out_dev, int64_t ldo, bool out_tiled, void* hip_stream)
 {
     if (!h || !X_dev || !ep || !out_dev) return SPMM_E_ARG;
     if (!h->on_device) return SPMM_E_ARG;   // packed with spmm_pack_host: nothing to run on
@@ -288,6 +291,16 @@ static spmm_status_t run_common(const spmm_handle_t* h, const uint8_t* X_dev, in
     }
     const int64_t esz = quant ? 1 : 4;
     a.out_vec_ok = aligned(out_dev, 16) && ((ldo * esz) % 16 == 0) && (h->bsr.N * ldo * esz < ((int64_t)1 << 31));
+    if (out_tiled) {
+        // token-tile-major 1-byte output: [ceil(M / 32)][N][32] bytes, 16-byte aligned
+        if (!quant) return SPMM_E_UNSUPPORTED;
+        if (!aligned(out_dev, 16)) return SPMM_E_ARG;
+        const int64_t tiles = (M + SPMM_X_TILE - 1) / SPMM_X_TILE;
+        if (tiles * h->bsr.N * SPMM_X_TILE >= ((int64_t)1 << 31)) return SPMM_E_UNSUPPORTED;
+        a.ldo = SPMM_X_TILE;
+        a.out_tile_stride = (int)(h->bsr.N * SPMM_X_TILE);
+        a.out_vec_ok = 1;
+    }
     if (ep->sum) {
         a.sum = ep->sum;
         a.ld_sum = ep->ld_sum;

@@ -88,6 +88,7 @@ struct KernelArgs {
     int x_vec_ok;        // X base 16-byte aligned, ldx % 16 == 0 and K * ldx < 2^31 (tile-major: the whole X < 2^31 bytes)
     int out_vec_ok;      // out base 16-byte aligned, row pitch a multiple of 16 bytes, whole output < 2^31 bytes
                          // (and, with Sum, the same for the second operand)
+    int out_tile_stride; // 0: out row-major [N][ldo]; else 1-byte out token-tile-major [ceil(M/32)][N][32], ldo = 32 and this = 32 N
     int x_tile_stride;   // 0: X row-major [K][ldx]; else X token-tile-major [ceil(M/32)][K][32], ldx = 32 and this = 32 K
 };
 

@@ -116,7 +116,8 @@ __device__ __forceinline__ uint32_t quantise(const KernelArgs& a, const float y,
 // WIDE: 1-byte outputs of an unaligned matrix are written in the widest pieces the address
 // allows (dword, two halves, bytes) instead of bytes; costs registers the 16-wave pipelined
 // kernels do not have (the host does not pick those for unaligned operands).
-template <int OUT, int POST, bool WIDE = false, typename Lut>
+// OT: layout of a 1-byte output: 1 = token-tile-major, 0 = row-major, -1 = whichever the arguments say
+template <int OUT, int POST, bool WIDE = false, int OT = -1, typename Lut>
 __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, const float s, const float b,
                                         const int n, const int m0, const Lut& lut)
 {
@@ -156,7 +157,11 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
             uint32_t q[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) q[r] = quantise<OUT, POST>(a, y[r], lut);
-            uint8_t* o = (uint8_t*)a.out + (int64_t)n * a.ldo + m0;
+            // (token-tile-major output, [M / 32][N][32]: rows 32 bytes apart, a column's tile out_tile_stride
+            // = 32 N bytes after the previous one; four consecutive tokens from a multiple of 4 share a tile)
+            const bool ot = (OT == 1) || (OT == -1 && a.out_tile_stride != 0);
+            uint8_t* o = (uint8_t*)a.out + (int64_t)n * a.ldo +
+                         (ot ? (int64_t)(m0 >> 5) * a.out_tile_stride + (m0 & 31) : (int64_t)m0);
             if (valid >= 4 && (a.out_vec_ok || (WIDE && ((uintptr_t)o & 3) == 0))) {
                 *(uint32_t*)o = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
             } else if (WIDE && valid >= 4 && ((uintptr_t)o & 1) == 0) {
@@ -323,7 +328,7 @@ struct LdsLut {
 // aligned: lane (g, c) holds tokens tok0 + 16 i + 4 g + {0..3} of output row 16 * tile + c.
 // 4-byte outputs are stored straight from the accumulator layout (16 bytes per lane, 64-byte
 // runs per row); 1-byte outputs go through the LDS staging chunks.
-template <int TM, int OUT, int POST>
+template <int TM, int OUT, int POST, int OT = -1>
 __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i (&acc)[Geo<TM>::PIECES],
                                                  const float scale, const float bias, const int tile,
                                                  const int tok0, int lane, const int wave, uint8_t* lds)
@@ -368,7 +373,13 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
         const int rr = lane >> 2, rj = lane & 3;
         const uint32_t raddr = G::chunk(64 * wave + 4 * rr + (rj ^ (rr >> 2)));
         const int orow = tile * TILE_ROWS + rr;
-        const uint32_t off = (uint32_t)orow * (uint32_t)a.ldo + (uint32_t)(tok0 + 16 * rj);
+        // row-major: 64-byte steps between the halves; token-tile-major ([M / 32][N][32], tok0 a multiple of 32):
+        // piece rj of half h lies in tile tok0 / 32 + rj / 2 + 2 h, at byte 16 (rj & 1) of the row
+        const bool ot = (OT == 1) || (OT == -1 && a.out_tile_stride != 0);
+        const uint32_t ots = (uint32_t)a.out_tile_stride;
+        const uint32_t off = ot ? (uint32_t)((tok0 >> 5) + (rj >> 1)) * ots + (uint32_t)orow * 32u + (uint32_t)((rj & 1) * 16)
+                                : (uint32_t)orow * (uint32_t)a.ldo + (uint32_t)(tok0 + 16 * rj);
+        const uint32_t half_step = ot ? 2u * ots : 64u;
         uint8_t* o = (uint8_t*)a.out + off;
         // (Sum: read in the accumulator layout, row 16 * tile + c; rows past N are never stored)
         const bool sum_row_ok = tile * TILE_ROWS + c < a.N;
@@ -393,15 +404,17 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
                 *(uint32_t*)(lds + wbase + (uint32_t)(j ^ wsw) * G::STRIDE) = word;
             }
             const v4i v = *(const v4i*)(lds + raddr);   // same wave: LDS operations complete in order
-            if (orow < a.N && 4 * h + rj < G::PIECES) *(v4i*)(o + 64 * h) = v;
+            if (orow < a.N && 4 * h + rj < G::PIECES) *(v4i*)(o + half_step * h) = v;
         }
     }
 }
 
-template <int TM, int NW, int MAXS, int OUT, int POST, int XT = 0>
+template <int TM, int NW, int MAXS, int OUT, int POST, int LAYOUT = 0>
 __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
 {
     using G = Geo<TM>;
+    // LAYOUT bit 0: activations token-tile-major; bit 1: (1-byte) outputs token-tile-major
+    constexpr int XT = LAYOUT & 1, OTILED = (LAYOUT >> 1) & 1;
     constexpr int NTHREADS = NW * 64;
     constexpr int PIECES = G::PIECES;
     // activation rows one load pass covers: a power of two; with 6 pieces per row only
@@ -581,13 +594,13 @@ __global__ void __launch_bounds__(NW * 64) spmm_rowtile_mfma(const KernelArgs a)
         const int tok0 = (stream + j * S) * TM;
         if (have_tile) {
             if (a.out_vec_ok && tok0 + TM <= a.M) {
-                finish_tile_fast<TM, OUT, POST>(a, acc, scale, bias, tile, tok0, lane, wave, lds);
+                finish_tile_fast<TM, OUT, POST, OTILED>(a, acc, scale, bias, tile, tok0, lane, wave, lds);
             } else if (n < a.N) {
                 const LdsLut<TM> lut{lds};
 #pragma unroll
                 for (int i = 0; i < PIECES; ++i) {
                     const int m0 = tok0 + 16 * i + 4 * g;
-                    if (m0 < a.M) finish4<OUT, POST, NW != 16>(a, acc[i], scale, bias, n, m0, lut);
+                    if (m0 < a.M) finish4<OUT, POST, NW != 16, OTILED>(a, acc[i], scale, bias, n, m0, lut);
                 }
             }
         }

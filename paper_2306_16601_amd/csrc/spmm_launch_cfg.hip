@@ -131,8 +131,14 @@ struct PipeLaunch {
     template <int OUT, int POST>
     static void go(dim3 grid, dim3 block, hipStream_t st, const KernelArgs& a)
     {
-        // one instantiation per activation layout (row-major / token-tile-major)
-        if (a.x_tile_stride) hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST, 1>), grid, block, 0, st, a);
+        // one instantiation per layout of the activations and of 1-byte outputs (row-major / token-tile-major):
+        // the 16-wave forms have no register to spare for a choice at run time
+        const int layout = (a.x_tile_stride ? 1 : 0) | (a.out_tile_stride ? 2 : 0);
+        if constexpr (OUT == SPMM_OUT_S8 || OUT == SPMM_OUT_U8) {
+            if (layout == 3) { hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST, 3>), grid, block, 0, st, a); return; }
+            if (layout == 2) { hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST, 2>), grid, block, 0, st, a); return; }
+        }
+        if (layout & 1) hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST, 1>), grid, block, 0, st, a);
         else hipLaunchKernelGGL((spmm_rowtile_mfma<TM, NW, MAXS, OUT, POST, 0>), grid, block, 0, st, a);
     }
 };

@@ -21,7 +21,8 @@ def main():
     sparsity, ot, po = float(sys.argv[4]), sys.argv[5], sys.argv[6]
     tm, var, ldx, ldo, cus = (int(v) for v in sys.argv[7:12])
     kind = sys.argv[12] if len(sys.argv) > 12 else "uniform"
-    x_tiled = len(sys.argv) > 13 and sys.argv[13] == "xtiled"
+    x_tiled = len(sys.argv) > 13 and sys.argv[13] in ("xtiled", "xotiled")
+    o_tiled = len(sys.argv) > 13 and sys.argv[13] == "xotiled"
     os.environ["EMU_CUS"] = str(cus)
     import build_emu
     import paper_2306_16601_amd.binding as b
@@ -62,7 +63,8 @@ def main():
     ep = sp.make_epilogue(dev(d["w_scale"]), d["x_scale"], d["x_zero_point"], dev(d["bias"]), po, ot,
                           d["out_scale"], d["out_zero_point"], d["mid_scale"], lut)
     dt = {"s32": np.int32, "f32": np.float32, "s8": np.int8, "u8": np.uint8}[ot]
-    nbytes = N * ldo * np.dtype(dt).itemsize
+    tiles = (M + 31) // 32
+    nbytes = tiles * N * 32 if o_tiled else N * ldo * np.dtype(dt).itemsize
     od = L.emu_alloc(nbytes)
     ctypes.memset(od, 0x5A, nbytes)
     if x_tiled:
@@ -70,11 +72,18 @@ def main():
         # the padding of the last tile is poisoned
         Xt = sp.tile_major(X)
         Xt[-1, :, M - 32 * (Xt.shape[0] - 1):] = 0xEE
-        sp.spmm_run_tiled(h, dev(Xt), M, ep, od, ldo, None)
+        sp.spmm_run_tiled(h, dev(Xt), M, 0, ep, od, ldo, 3 if o_tiled else 1, None)
     else:
         sp.spmm_run(h, dev(Xp), M, ldx, ep, od, ldo, None)
-    full = np.empty((N, ldo), dtype=dt)
-    ctypes.memmove(full.ctypes.data, od, nbytes)
+    if o_tiled:
+        raw = np.empty(nbytes, dtype=dt)
+        ctypes.memmove(raw.ctypes.data, od, nbytes)
+        T = raw.reshape(tiles, N, 32)
+        full = np.full((N, tiles * 32 + 1), 0x5A, dtype=dt)      # (one extra column: the padding check below)
+        full[:, :tiles * 32] = T.transpose(1, 0, 2).reshape(N, tiles * 32)
+    else:
+        full = np.empty((N, ldo), dtype=dt)
+        ctypes.memmove(full.ctypes.data, od, nbytes)
     got = full[:, :M]
     ref = oracle.spmm(W, X, d["w_scale"], d["x_scale"], d["bias"], po, ot, d["out_scale"], d["out_zero_point"],
                       d["mid_scale"], d["x_zero_point"])

@@ -33,8 +33,9 @@ def emu_lib():
 
 
 def run_case(N, K, M, sparsity, out_type, postop, tm, variant, ldx=0, ldo=0, cus=4, kind="uniform", xtiled=False):
+    # xtiled: True = tile-major activations, "out" = tile-major activations and tile-major 1-byte output
     cmd = [sys.executable, os.path.join(HERE, "emu", "run_case.py"), str(N), str(K), str(M), str(sparsity), out_type,
-           postop, str(tm), str(variant), str(ldx), str(ldo), str(cus), kind] + (["xtiled"] if xtiled else [])
+           postop, str(tm), str(variant), str(ldx), str(ldo), str(cus), kind] + (["xotiled"] if xtiled == "out" else ["xtiled"] if xtiled else [])
     r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, "emulated kernel run failed (rc %d):\n%s" % (r.returncode, r.stderr[-3000:])
     return json.loads(r.stdout.strip().splitlines()[-1])
@@ -62,6 +63,9 @@ CASES = [
     (128, 700, 150, 0.8, "s8", "none", 64, 101, "spmm_rowtile_mfma_simple<64", {"xtiled": True}),
     (128, 2560, 40, 0.9, "s32", "none", 16, 103, "spmm_rowtile_mfma_slab<16", {"xtiled": True}),
     (128, 3584, 70, 0.9, "s8", "gelu", 32, 104, "spmm_rowtile_mfma_stream<32", {"xtiled": True}),
+    (300, 1000, 333, 0.85, "s8", "gelu", 128, 16, "spmm_rowtile_mfma<128, 16", {"cus": 2, "xtiled": "out"}),
+    (272, 1536, 200, 0.9, "u8", "none", 96, 112, "spmm_rowtile_mfma_fed<96, 12", {"cus": 2, "xtiled": "out"}),
+    (128, 700, 150, 0.8, "s8", "none", 32, 101, "spmm_rowtile_mfma_simple<32", {"xtiled": "out"}),
     # simple kernel at its three tile widths
     (256, 1024, 192, 0.9, "s8", "gelu", 64, 101, "spmm_rowtile_mfma_simple<64", {}),
     (512, 768, 128, 0.8, "s32", "none", 64, 102, "spmm_rowtile_mfma_simple<64", {}),

@@ -53,7 +53,7 @@ def gpu_spmm(W, X, d, case, ldx=None, ldo=None, tuning=None, stream=None, x_offs
         if x_tiled:
             Xt = dev(sp.tile_major(X))
             Xt[-1, :, M - sp.binding.SPMM_X_TILE * (Xt.shape[0] - 1):] = 0xEE      # the padding of the last tile must never matter
-            sp.spmm_run_tiled(h, Xt, M, ep, oview, ldo, st)
+            sp.spmm_run_tiled(h, Xt, M, 0, ep, oview, ldo, sp.binding.SPMM_TILED_X, st)
         else:
             sp.spmm_run(h, Xv, M, ldx, ep, oview, ldo, st)
         torch.cuda.synchronize()
@@ -645,6 +645,86 @@ def test_tile_major_large_case_and_argument_errors():
         Xt = dev(sp.tile_major(d["X"]))
         out = torch.zeros((256, 128), dtype=torch.int32, device="cuda")
         with pytest.raises(sp.SpmmError):                        # activations must be 16-byte aligned
-            sp.spmm_run_tiled(h, Xt.view(-1)[1:], 100, ep, out, 128, None)
+            sp.spmm_run_tiled(h, Xt.view(-1)[1:], 100, 0, ep, out, 128, sp.binding.SPMM_TILED_X, None)
     finally:
         sp.spmm_destroy(h)
+
+
+def _run_tiled_out(d, case, tuning, x_tiled):
+    """1-byte output written token-tile-major into an exactly sized, guarded buffer; returned row-major."""
+    W, X = d["W"], d["X"]
+    N, K = W.shape
+    M = X.shape[1]
+    ot = case.out_type
+    h = sp.spmm_pack(W, case.orientation)
+    try:
+        if tuning:
+            sp.spmm_set_tuning(h, *tuning)
+        tiles = (M + 31) // 32
+        obuf = torch.full((tiles * N * 32 + 2 * GUARD,), POISON[ot], dtype=TORCH_DT[ot], device="cuda")
+        oview = obuf[GUARD:GUARD + tiles * N * 32]
+        lut = None
+        if case.postop == "gelu":
+            lut = dev(sp.spmm_make_gelu_lut(d["mid_scale"], d["out_scale"], d["out_zero_point"], ot))
+        ep = sp.make_epilogue(dev(d["w_scale"]), d["x_scale"], d["x_zero_point"], dev(d["bias"]), case.postop, ot,
+                              d["out_scale"], d["out_zero_point"], d["mid_scale"], lut)
+        Xd = dev(sp.tile_major(X)) if x_tiled else dev(X)
+        flags = sp.binding.SPMM_TILED_OUT | (sp.binding.SPMM_TILED_X if x_tiled else 0)
+        sp.spmm_run_tiled(h, Xd, M, M, ep, oview, 0, flags, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        full = obuf.cpu().numpy()
+        poison = np.array(POISON[ot]).astype(full.dtype)
+        assert (full[:GUARD] == poison).all() and (full[GUARD + tiles * N * 32:] == poison).all()
+        T = full[GUARD:GUARD + tiles * N * 32].reshape(tiles, N, 32)
+        if M % 32:
+            assert (T[-1, :, M % 32:] == poison).all()          # the padding of the last tile is not written
+        return sp.from_tile_major(T, M)
+    finally:
+        sp.spmm_destroy(h)
+
+
+@pytest.mark.parametrize("tuning", [None, (128, 16), (128, 8), (96, 16), (128, 112), (128, 108), (64, 112), (64, 101), (32, 101),
+                                    (16, 101), (16, 103), (32, 103), (64, 104), (16, 104)],
+                         ids=lambda t: "auto" if t is None else "%d_%d" % t)
+@pytest.mark.parametrize("N,K,M,s,out_type,postop,x_tiled", [(272, 1100, 704, 0.9, "s8", "gelu", True), (100, 600, 333, 0.8, "u8", "none", False),
+                                                              (512, 1536, 1280, 0.8, "s8", "none", True), (64, 520, 50, 0.7, "u8", "gelu", True)])
+def test_tile_major_output(N, K, M, s, out_type, postop, x_tiled, tuning):
+    """SPMM_TILED_OUT writes the 1-byte output as the next layer's tile-major activations: same values as the
+    oracle's row-major output, nothing outside the tiles, in every kernel family."""
+    case = wl.Case("otiled", N, K, M, s, wl.N4K1, out_type, postop, keys=(84, N, K, M))
+    d = wl.make(case)
+    got = _run_tiled_out(d, case, tuning, x_tiled)
+    assert_parity(got, oracle_spmm(d["W"], d["X"], d, case), case)
+
+
+def test_chained_ffn_pair_in_tile_major_order():
+    """The chained pair of Section 3.3 with every activation tile-major: layer 1 reads tile-major X and writes its
+    u8 code tile-major, layer 2 reads that buffer as is; both bit-equal to the oracle chained the same way."""
+    c1, c2 = wl.chain_cases()
+    d1, d2 = wl.make_chain([c1, c2])
+    M = c1.M
+    ref1 = oracle_spmm(d1["W"], d1["X"], d1, c1)
+    ref2 = oracle_spmm(d2["W"], ref1, d2, c2)
+    h1, h2 = sp.spmm_pack(d1["W"]), sp.spmm_pack(d2["W"])
+    try:
+        st = torch.cuda.current_stream().cuda_stream
+        lut = dev(sp.spmm_make_gelu_lut(d1["mid_scale"], d1["out_scale"], d1["out_zero_point"], "u8"))
+        ep1 = sp.make_epilogue(dev(d1["w_scale"]), d1["x_scale"], 0, dev(d1["bias"]), "gelu", "u8", d1["out_scale"],
+                               d1["out_zero_point"], d1["mid_scale"], lut)
+        ep2 = sp.make_epilogue(dev(d2["w_scale"]), d2["x_scale"], d2["x_zero_point"], dev(d2["bias"]), "none", "s8",
+                               d2["out_scale"], 0, d2["mid_scale"], None)
+        hid = torch.zeros(((M + 31) // 32) * c1.N * 32, dtype=torch.uint8, device="cuda")
+        out = torch.zeros((c2.N, M), dtype=torch.int8, device="cuda")
+        both = sp.binding.SPMM_TILED_X | sp.binding.SPMM_TILED_OUT
+        sp.spmm_run_tiled(h1, dev(sp.tile_major(d1["X"])), M, 0, ep1, hid, 0, both, st)
+        sp.spmm_run_tiled(h2, hid, M, 0, ep2, out, M, sp.binding.SPMM_TILED_X, st)
+        torch.cuda.synchronize()
+        got1 = sp.from_tile_major(hid.cpu().numpy().reshape(-1, c1.N, 32), M)
+        assert np.array_equal(got1, ref1)
+        assert np.array_equal(out.cpu().numpy(), ref2)
+        with pytest.raises(sp.SpmmError):                        # 4-byte outputs have no tile-major form
+            ep3 = sp.make_epilogue(dev(d2["w_scale"]), d2["x_scale"], 0, None, "none", "f32", 1.0, 0, 1.0, None)
+            sp.spmm_run_tiled(h2, hid, M, 0, ep3, torch.zeros((c2.N, M), dtype=torch.float32, device="cuda"), M, both, st)
+    finally:
+        sp.spmm_destroy(h1)
+        sp.spmm_destroy(h2)
