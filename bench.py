@@ -180,6 +180,23 @@ def time_base_f32(np, torch, sp, wl, steps, with_dense):
     return {"workload": "bert_base_layers_m4096_s90_s80_f32", "launch_mode": "eager_back_to_back", "per_call": rows}
 
 
+def make_bufs(torch, sp, d, case, N, prev, flags):
+    """ROTATE device copies of the activations and ROTATE output buffers of one call, in the layout `flags` names
+    (SPMM_TILED_X / SPMM_TILED_OUT).  A chained call (d["X"] is None) reads the previous call's output buffers of
+    the same layout."""
+    tdt = {"s32": torch.int32, "f32": torch.float32, "s8": torch.int8, "u8": torch.uint8}
+    if d["X"] is None:
+        xs = prev["bufs"][flags | (sp.binding.SPMM_TILED_OUT if flags & sp.binding.SPMM_TILED_X else 0)][1]
+    else:
+        xh = sp.tile_major(d["X"]) if flags & sp.binding.SPMM_TILED_X else d["X"]
+        xs = [torch.from_numpy(xh).cuda() for _ in range(ROTATE)]
+    if flags & sp.binding.SPMM_TILED_OUT:
+        outs = [torch.empty(((case.M + 31) // 32) * N * 32, dtype=tdt[case.out_type], device="cuda") for _ in range(ROTATE)]
+    else:
+        outs = [torch.empty((N, case.M), dtype=tdt[case.out_type], device="cuda") for _ in range(ROTATE)]
+    return xs, outs
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -197,7 +214,10 @@ def main() -> int:
     ap.add_argument("--reorder", action="store_true",
                     help="pack with SPMM_PACK_REORDER_ROWS (rows clustered by k overlap); outputs and per-row "
                          "operands are then in the library's row order")
-    ap.add_argument("--no-tile-major", action="store_true", help="skip the extra timing with token-tile-major activations")
+    ap.add_argument("--layout", default="tile_major", choices=["tile_major", "row_major"],
+                    help="activation layout of the timed steps: token-tile-major [M/32][rows][32] for X and for 1-byte "
+                         "outputs (the library's own layout between layers: spmm_run_tiled), or plain row-major")
+    ap.add_argument("--no-other-layout", action="store_true", help="skip the extra timing of the same steps in the other layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--tuning", default="", help="token_tile,variant override passed to spmm_set_tuning")
@@ -306,9 +326,15 @@ def main() -> int:
                                     d["out_scale"], d["out_zero_point"], d["mid_scale"], lut)] * ROTATE
         ep = eps[0]
         # (chained pair: the second launch reads the first launch's output buffers)
-        Xs = calls[-1]["outs"] if d["X"] is None else [torch.from_numpy(d["X"]).cuda() for _ in range(ROTATE)]
-        outs = [torch.empty((N, case.M), dtype=tdt[case.out_type], device="cuda") for _ in range(ROTATE)]
+        # layout flags of this call: tile-major X, and tile-major output where it is a 1-byte one
+        tiled = 0
+        if args.layout == "tile_major":
+            tiled = sp.binding.SPMM_TILED_X | (sp.binding.SPMM_TILED_OUT if case.out_type in ("s8", "u8") else 0)
+
+        prev = calls[-1] if calls else None
+        Xs, outs = make_bufs(torch, sp, d, case, N, prev, tiled)
         calls.append(dict(case=case, d=d, h=h, ep=ep, eps=eps, keep=(ws, bias, lut, Rs), Xs=Xs, outs=outs, N=N, K=K,
+                          tiled=tiled, bufs={tiled: (Xs, outs)}, prev=prev,
                           M=case.M, nnzb=nnzb, padded=padded, dev_bytes=dev_bytes,
                           bytes=algorithmic_bytes(N, K, case.M, nnzb, out_elem[case.out_type]) +
                           (4 * N * case.M if Rs else 0),
@@ -318,8 +344,8 @@ def main() -> int:
     # arguments marshalled once per (call, rotation): a launch is then one C call
     stream = torch.cuda.current_stream().cuda_stream
     for c in calls:
-        c["run"] = [sp.spmm_run_bound(c["h"], c["Xs"][j], c["M"], c["M"], c["eps"][j], c["outs"][j], c["M"], stream)
-                    for j in range(ROTATE)]
+        c["run"] = [sp.spmm_run_tiled_bound(c["h"], c["Xs"][j], c["M"], c["M"], c["eps"][j], c["outs"][j], c["M"],
+                                            c["tiled"], stream) for j in range(ROTATE)]
 
     def launch(c, it):
         if c["run"][it % ROTATE]() != 0:
@@ -371,7 +397,7 @@ def main() -> int:
                 with torch.cuda.graph(g):
                     cap = torch.cuda.current_stream().cuda_stream      # the capturing stream
                     for c in calls:
-                        sp.spmm_run(c["h"], c["Xs"][j], c["M"], c["M"], c["eps"][j], c["outs"][j], c["M"], cap)
+                        sp.spmm_run_tiled(c["h"], c["Xs"][j], c["M"], c["M"], c["eps"][j], c["outs"][j], c["M"], c["tiled"], cap)
                 graphs.append(g)
             for it in range(max(2, args.warmup // 2)):
                 graphs[it % ROTATE].replay()
@@ -416,34 +442,45 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         b2b_us.append(e0.elapsed_time(e1) * 1e3 / args.steps)
-    # ------------------------------------------------------------------ extra: the same steps with the activations
-    # handed over in token-tile-major order (spmm_run_tiled), eager back to back and with events per launch
-    tile_major = None
-    if not args.profile and all(c["d"]["X"] is not None for c in calls) and not args.no_tile_major:
+    # ------------------------------------------------------------------ extra: the same steps in the OTHER activation
+    # layout (row-major when the timed steps are tile-major and vice versa), eager back to back + events per launch
+    other_layout = None
+    if not args.profile and not args.no_other_layout:
+        other = "row_major" if args.layout == "tile_major" else "tile_major"
+
+        def flags_of(c):
+            if other == "row_major":
+                return 0
+            return sp.binding.SPMM_TILED_X | (sp.binding.SPMM_TILED_OUT if c["case"].out_type in ("s8", "u8") else 0)
         for c in calls:
-            xt = sp.tile_major(c["d"]["X"])
-            c["Xt"] = [torch.from_numpy(xt).cuda() for _ in range(ROTATE)]
-            c["run_t"] = [sp.spmm_run_tiled_bound(c["h"], c["Xt"][j], c["M"], c["M"], c["eps"][j], c["outs"][j], c["M"], sp.binding.SPMM_TILED_X, stream)
+            f = flags_of(c)
+            if f not in c["bufs"]:
+                c["bufs"][f] = make_bufs(torch, sp, c["d"], c["case"], c["N"], c["prev"], f)
+            xs, os_ = c["bufs"][f]
+            c["run_o"] = [sp.spmm_run_tiled_bound(c["h"], xs[j], c["M"], c["M"], c["eps"][j], os_[j], c["M"], f, stream)
                           for j in range(ROTATE)]
-        # (results first: bit-identical to the row-major launch of the same call)
+        for it in range(max(2, args.warmup // 2)):
+            for c in calls:
+                c["run_o"][it % ROTATE]()
+        torch.cuda.synchronize()
+        # the two layouts hold the same values
         same = True
         for c in calls:
             launch(c, 0)
-            torch.cuda.synchronize()
-            ref_out = c["outs"][0].clone()
-            c["outs"][0].zero_()
-            c["run_t"][0]()
-            torch.cuda.synchronize()
-            same &= bool(torch.equal(ref_out.view(torch.uint8), c["outs"][0].view(torch.uint8)))
-        for it in range(max(2, args.warmup // 2)):
-            for c in calls:
-                c["run_t"][it % ROTATE]()
+        for c in calls:
+            c["run_o"][0]()
         torch.cuda.synchronize()
+        for c in calls:
+            def rows(buf, flags):
+                a_ = buf.cpu().numpy()
+                return sp.from_tile_major(a_.reshape(-1, c["N"], 32), c["M"]) if flags & sp.binding.SPMM_TILED_OUT else a_
+            same &= bool(np.array_equal(rows(c["outs"][0], c["tiled"]).view(np.uint8),
+                                        rows(c["bufs"][flags_of(c)][1][0], flags_of(c)).view(np.uint8)))
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for it in range(args.steps):
             for c in calls:
-                c["run_t"][it % ROTATE]()
+                c["run_o"][it % ROTATE]()
         e1.record()
         torch.cuda.synchronize()
         t_ms = e0.elapsed_time(e1) / args.steps
@@ -451,43 +488,20 @@ def main() -> int:
         for it in range(args.steps):
             evt[it][0].record()
             for ci, c in enumerate(calls):
-                c["run_t"][it % ROTATE]()
+                c["run_o"][it % ROTATE]()
                 evt[it][ci + 1].record()
         torch.cuda.synchronize()
         t_ev_ms = evt[0][0].elapsed_time(evt[args.steps - 1][nc]) / args.steps
         t_call = np.array([[evt[it][ci].elapsed_time(evt[it][ci + 1]) * 1e3 for ci in range(nc)]
                            for it in range(args.steps)]).mean(axis=0) * (t_ms / t_ev_ms)
-        # ... and with the 1-byte outputs tile-major as well (what a chain of layers in this layout runs)
-        t2_ms = None
-        if all(c["case"].out_type in ("s8", "u8") and c["M"] % 32 == 0 for c in calls):
-            both = sp.binding.SPMM_TILED_X | sp.binding.SPMM_TILED_OUT
-            for c in calls:
-                c["run_t2"] = [sp.spmm_run_tiled_bound(c["h"], c["Xt"][j], c["M"], 0, c["eps"][j], c["outs"][j], 0, both, stream)
-                               for j in range(ROTATE)]
-            for it in range(max(2, args.warmup // 2)):
-                for c in calls:
-                    c["run_t2"][it % ROTATE]()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for it in range(args.steps):
-                for c in calls:
-                    c["run_t2"][it % ROTATE]()
-            e1.record()
-            torch.cuda.synchronize()
-            t2_ms = e0.elapsed_time(e1) / args.steps
-            for c in calls:
-                del c["run_t2"]
-        tile_major = {"layout": "X as [ceil(M/32)][K][32] (spmm_run_tiled), outputs row-major",
-                      "ms_per_step_with_tile_major_outputs_too": None if t2_ms is None else round(t2_ms, 5),
-                      "ms_per_step": round(t_ms, 5),
-                      "value": round(sum(c["dense_ops"] for c in calls) / (t_ms * 1e-3) / 1e12, 2),
-                      "same_bits_as_row_major": same,
-                      "per_call_us_in_step": {c["case"].name: round(float(t_call[i]), 2) for i, c in enumerate(calls)},
-                      "per_call_roofline_frac_in_step": {c["case"].name: round(c["bytes"] / (float(t_call[i]) * 1e-6) / (HBM_PEAK_GBS * 1e9), 4)
-                                                         for i, c in enumerate(calls)}}
+        other_layout = {"layout": other, "ms_per_step": round(t_ms, 5),
+                        "value": round(sum(c["dense_ops"] for c in calls) / (t_ms * 1e-3) / 1e12, 2),
+                        "same_values_in_both_layouts": same,
+                        "per_call_us_in_step": {c["case"].name: round(float(t_call[i]), 2) for i, c in enumerate(calls)},
+                        "per_call_roofline_frac_in_step": {c["case"].name: round(c["bytes"] / (float(t_call[i]) * 1e-6) / (HBM_PEAK_GBS * 1e9), 4)
+                                                           for i, c in enumerate(calls)}}
         for c in calls:
-            del c["Xt"], c["run_t"]
+            del c["run_o"]
 
     # `value` and the roofline use ONE launch mode: plain eager launches back to back on the stream (what a
     # caller of spmm_run gets; graph replay of the same steps is reported beside it)
@@ -597,7 +611,7 @@ def main() -> int:
     # its launches / their summed durations = bytes per launch / average launch duration
     by_kernel = {}
     for ci, c in enumerate(calls):
-        name = sp.spmm_kernel_variant(c["h"], c["M"], c["case"].out_type, c["case"].postop)
+        name = sp.spmm_kernel_variant(c["h"], c["M"], c["case"].out_type, c["case"].postop, c["tiled"])
         k = by_kernel.setdefault(name, {"bytes": 0.0, "us": 0.0, "launches": 0, "nnz_ops": 0.0})
         k["bytes"] += c["bytes"]
         k["us"] += float(avg_us[ci]) * gap_scale
@@ -648,6 +662,8 @@ def main() -> int:
             launch(c, 0)
             torch.cuda.synchronize()
             got = c["outs"][0].cpu().numpy()
+            if c["tiled"] & sp.binding.SPMM_TILED_OUT:
+                got = sp.from_tile_major(got.reshape(-1, c["N"], 32), c["M"])
             t1 = time.perf_counter()
             ref = oracle.spmm(d["W"], d["X"] if d["X"] is not None else prev_ref, d["w_scale"], d["x_scale"], d["bias"],
                               case.postop, case.out_type, d["out_scale"], d["out_zero_point"], d["mid_scale"],
@@ -695,11 +711,13 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": wname, "calls_per_step": nc, "tokens": calls[0]["M"], "orientation": "n4k1",
-                   "buffer_rotation": ROTATE},
+                   "buffer_rotation": ROTATE,
+                   "activation_layout": ("token-tile-major [M/32][rows][32]: X, and the 1-byte outputs a next layer reads "
+                                         "(spmm_run_tiled)") if args.layout == "tile_major" else "row-major"},
         "nonzero_tops": round(nnz_tops, 2),
         "roofline": roofline, "cpu_baseline": cpu, "dense_int8_gemm": dense, "qkv_stacked": qkv, "per_call": rows,
         "base_f32": base_f32,
-        "tile_major_x": tile_major,
+        "other_layout": other_layout,
         "ms_per_step_eager_with_events": round(eager_ms_per_step, 5),
         "ms_per_step_graph": (round(graph_ms_per_step, 5) if graph_ms_per_step is not None else None),
         "ms_per_step_eager_back_to_back": round(stream_ms_per_step, 5),

@@ -250,6 +250,10 @@ const char *spmm_kernel_name(void);
  * NUL-terminated and truncated if it does not fit. */
 spmm_status_t spmm_kernel_variant(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
                                   spmm_postop_t postop, char *buf, int64_t buflen);
+/* The same for spmm_run_tiled with these layout flags (for profilers; the callers are the
+ * benchmark and the tests). */
+spmm_status_t spmm_kernel_variant_tiled(const spmm_handle_t *h, int64_t M, spmm_out_t out_type,
+                                        spmm_postop_t postop, uint32_t tiled, char *buf, int64_t buflen);
 
 /* Measured ceiling of a candidate multiply instruction on the current device, registers only
  * (Section 3.2 builds the kernel around the widest integer multiply-accumulate the hardware has;

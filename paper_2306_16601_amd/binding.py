@@ -26,10 +26,13 @@ BLOCKS = {"n4k1": SPMM_BLOCK_N4K1, "n1k4": SPMM_BLOCK_N1K4}
 POSTOPS = {"none": SPMM_POST_NONE, "gelu": SPMM_POST_GELU, "table": SPMM_POST_TABLE}
 OUT_TYPES = {"s32": SPMM_OUT_S32, "f32": SPMM_OUT_F32, "s8": SPMM_OUT_S8, "u8": SPMM_OUT_U8}
 
+SPMM_X_TILE = 32                         # tokens per tile of the tile-major activation layout
+SPMM_TILED_X, SPMM_TILED_OUT = 1, 2     # layout flags of spmm_run_tiled
+
 EXPORTS = (
     "spmm_pack", "spmm_pack_host", "spmm_pack_ex", "spmm_row_order", "spmm_unpack", "spmm_info", "spmm_layout_dims",
     "spmm_layout_export", "spmm_run", "spmm_run_tiled", "spmm_make_gelu_lut", "spmm_plan", "spmm_set_tuning",
-    "spmm_kernel_name", "spmm_kernel_variant", "spmm_measure_peak", "spmm_destroy", "spmm_status_string",
+    "spmm_kernel_name", "spmm_kernel_variant", "spmm_kernel_variant_tiled", "spmm_measure_peak", "spmm_destroy", "spmm_status_string",
 )
 
 
@@ -99,6 +102,8 @@ def lib() -> ctypes.CDLL:
         L.spmm_kernel_name.argtypes = []
         L.spmm_kernel_variant.restype = ci
         L.spmm_kernel_variant.argtypes = [vp, i64, ci, ci, ctypes.c_char_p, i64]
+        L.spmm_kernel_variant_tiled.restype = ci
+        L.spmm_kernel_variant_tiled.argtypes = [vp, i64, ci, ci, ctypes.c_uint32, ctypes.c_char_p, i64]
         L.spmm_measure_peak.restype = ci
         L.spmm_measure_peak.argtypes = [i32, P(ctypes.c_double)]
         L.spmm_destroy.restype = None
@@ -117,6 +122,36 @@ def _dev_ptr(x) -> Optional[int]:
     return int(x)
 
 
+def _nbytes(x) -> Optional[int]:
+    """Bytes from a tensor-like argument's data pointer to the end of its storage view, or None for a raw address."""
+    if x is None or not hasattr(x, "data_ptr"):
+        return None
+    if hasattr(x, "untyped_storage") and hasattr(x, "storage_offset"):      # torch: what lies behind data_ptr()
+        return int(x.untyped_storage().nbytes()) - int(x.storage_offset()) * int(x.element_size())
+    if hasattr(x, "nbytes"):
+        return int(x.nbytes)
+    return None
+
+
+def _check_extents(handle: int, X_dev, M: int, ldx: int, ep, out_dev, ldo: int, tiled: int) -> None:
+    """Marshalling-side guard: when X / out / the Sum operand are tensors (not raw addresses), the memory
+    behind them must cover what the kernels will touch -- a buffer built for another shape is an error
+    here instead of a memory fault on the device."""
+    N, K = spmm_info(handle)[:2]
+    M, ldx, ldo = int(M), int(ldx), int(ldo)
+    if M <= 0:
+        return                                               # the library rejects it
+    tiles = (M + SPMM_X_TILE - 1) // SPMM_X_TILE
+    need_x = tiles * K * SPMM_X_TILE if tiled & SPMM_TILED_X else (K - 1) * ldx + M
+    esz = 4 if ep is not None and int(ep.out_type) in (SPMM_OUT_S32, SPMM_OUT_F32) else 1
+    need_o = tiles * N * SPMM_X_TILE if tiled & SPMM_TILED_OUT else ((N - 1) * ldo + M) * esz
+    for name, t, need in (("X", X_dev, need_x), ("out", out_dev, need_o)):
+        have = _nbytes(t)
+        if have is not None and have < need:
+            raise ValueError("spmm_run: %s holds %d bytes behind its data pointer, the call touches %d "
+                             "(N=%d K=%d M=%d ldx=%d ldo=%d tiled=%d)" % (name, have, need, N, K, M, ldx, ldo, tiled))
+
+
 def _check(status: int, where: str) -> None:
     if status != SPMM_OK:
         raise SpmmError(status, where)
@@ -130,11 +165,11 @@ def spmm_kernel_name() -> str:
     return lib().spmm_kernel_name().decode()
 
 
-def spmm_kernel_variant(handle: int, M: int, out_type="s32", postop="none") -> str:
+def spmm_kernel_variant(handle: int, M: int, out_type="s32", postop="none", tiled: int = 0) -> str:
     ot = OUT_TYPES[out_type] if isinstance(out_type, str) else int(out_type)
     po = POSTOPS[postop] if isinstance(postop, str) else int(postop)
     buf = ctypes.create_string_buffer(256)
-    _check(lib().spmm_kernel_variant(handle, int(M), ot, po, buf, 256), "spmm_kernel_variant")
+    _check(lib().spmm_kernel_variant_tiled(handle, int(M), ot, po, int(tiled), buf, 256), "spmm_kernel_variant")
     return buf.value.decode()
 
 
@@ -273,10 +308,8 @@ def spmm_run_status(handle: int, X_dev, M: int, ldx: int, ep: Optional[spmm_epil
 
 def spmm_run(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, out_dev, ldo: int, stream=None) -> None:
     """out = postops(W . X), asynchronous on `stream` (a raw hipStream_t value, None = default stream)."""
+    _check_extents(handle, X_dev, M, ldx, ep, out_dev, ldo, 0)
     _check(spmm_run_status(handle, X_dev, M, ldx, ep, out_dev, ldo, stream), "spmm_run")
-
-
-SPMM_X_TILE = 32
 
 
 def tile_major(X: np.ndarray) -> np.ndarray:
@@ -295,13 +328,11 @@ def from_tile_major(T: np.ndarray, M: int) -> np.ndarray:
     return np.ascontiguousarray(T.transpose(1, 0, 2).reshape(R, tiles * w)[:, :M])
 
 
-SPMM_TILED_X, SPMM_TILED_OUT = 1, 2
-
-
 def spmm_run_tiled(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, out_dev, ldo: int, tiled: int,
                    stream=None) -> None:
     """spmm_run with X (SPMM_TILED_X) and / or a 1-byte output (SPMM_TILED_OUT) in token-tile-major order."""
     st = None if stream is None else int(stream)
+    _check_extents(handle, X_dev, M, ldx, ep, out_dev, ldo, int(tiled))
     _check(int(lib().spmm_run_tiled(handle, _dev_ptr(X_dev), int(M), int(ldx), ctypes.byref(ep), _dev_ptr(out_dev),
                                     int(ldo), int(tiled), st)), "spmm_run_tiled")
 
@@ -309,6 +340,7 @@ def spmm_run_tiled(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, ou
 def spmm_run_tiled_bound(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, out_dev, ldo: int, tiled: int,
                          stream=None):
     """spmm_run_tiled with its arguments marshalled once (see spmm_run_bound)."""
+    _check_extents(handle, X_dev, M, ldx, ep, out_dev, ldo, int(tiled))
     fn = lib().spmm_run_tiled
     args = (ctypes.c_void_p(handle), ctypes.c_void_p(_dev_ptr(X_dev)), ctypes.c_int64(int(M)), ctypes.c_int64(int(ldx)),
             ctypes.byref(ep), ctypes.c_void_p(_dev_ptr(out_dev)), ctypes.c_int64(int(ldo)), ctypes.c_uint32(int(tiled)),
@@ -324,6 +356,7 @@ def spmm_run_bound(handle: int, X_dev, M: int, ldx: int, ep: spmm_epilogue_t, ou
     """spmm_run with its arguments marshalled once: returns a callable that makes the C call and
     returns its status (for launch loops of microsecond kernels, where converting the arguments
     every time costs as much as the kernel).  The caller keeps the tensors and `ep` alive."""
+    _check_extents(handle, X_dev, M, ldx, ep, out_dev, ldo, 0)
     fn = lib().spmm_run
     args = (ctypes.c_void_p(handle), ctypes.c_void_p(_dev_ptr(X_dev)), ctypes.c_int64(int(M)), ctypes.c_int64(int(ldx)),
             ctypes.byref(ep), ctypes.c_void_p(_dev_ptr(out_dev)), ctypes.c_int64(int(ldo)),

@@ -337,7 +337,16 @@ const char* spmm_kernel_name(void) { return "spmm_rowtile_mfma"; }
 spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t out_type, spmm_postop_t postop,
                                   char* buf, int64_t buflen)
 {
+    return spmm_kernel_variant_tiled(h, M, out_type, postop, 0, buf, buflen);
+}
+
+spmm_status_t spmm_kernel_variant_tiled(const spmm_handle_t* h, int64_t M, spmm_out_t out_type, spmm_postop_t postop,
+                                        uint32_t tiled, char* buf, int64_t buflen)
+{
     if (!h || M <= 0 || !buf || buflen <= 0) return SPMM_E_ARG;
+    if (tiled & ~(uint32_t)(SPMM_TILED_X | SPMM_TILED_OUT)) return SPMM_E_ARG;
+    const bool quant_out = (out_type == SPMM_OUT_S8 || out_type == SPMM_OUT_U8);
+    if ((tiled & SPMM_TILED_OUT) && !quant_out) return SPMM_E_UNSUPPORTED;
     if (out_type < SPMM_OUT_S32 || out_type > SPMM_OUT_U8) return SPMM_E_ARG;
     if (postop != SPMM_POST_NONE && postop != SPMM_POST_GELU && postop != SPMM_POST_TABLE) return SPMM_E_ARG;
     if (postop == SPMM_POST_TABLE) postop = SPMM_POST_GELU;   // same kernels
@@ -357,8 +366,10 @@ spmm_status_t spmm_kernel_variant(const spmm_handle_t* h, int64_t M, spmm_out_t 
                       p.token_tile, p.waves, p.loaders, p.max_steps, (int)out_type, post);
     else
         // (8-wave configurations run 5-step weights with the 6-step instantiation)
-        std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma<%d, %d, %d, %d, %d>(spmm::KernelArgs)",
-                      p.token_tile, p.waves, (p.waves == 8 && p.max_steps == 5) ? 6 : p.max_steps, (int)out_type, post);
+        // (last parameter: the layout instantiation, bit 0 activations, bit 1 outputs tile-major)
+        std::snprintf(buf, (size_t)buflen, "void spmm::spmm_rowtile_mfma<%d, %d, %d, %d, %d, %d>(spmm::KernelArgs)",
+                      p.token_tile, p.waves, (p.waves == 8 && p.max_steps == 5) ? 6 : p.max_steps, (int)out_type, post,
+                      (int)tiled);
     return SPMM_OK;
 }
 

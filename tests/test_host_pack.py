@@ -268,8 +268,8 @@ def test_plan_picks_token_tile_and_waves_per_shape():
     assert kernel(768, 3072, 1024) == "void spmm::spmm_rowtile_mfma_slab<32, 8, 2, 1>(spmm::KernelArgs)"
     assert kernel(1024, 4096, 1024) == "void spmm::spmm_rowtile_mfma_stream<32, 8, 2, 1>(spmm::KernelArgs)"
     assert kernel(768, 768, 128, (64, 104)) == "void spmm::spmm_rowtile_mfma_stream<64, 8, 2, 1>(spmm::KernelArgs)"
-    assert kernel(768, 3072, 6144) == "void spmm::spmm_rowtile_mfma<96, 16, 4, 2, 1>(spmm::KernelArgs)"
-    assert kernel(4096, 1024, 6144) == "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1>(spmm::KernelArgs)"
+    assert kernel(768, 3072, 6144) == "void spmm::spmm_rowtile_mfma<96, 16, 4, 2, 1, 0>(spmm::KernelArgs)"
+    assert kernel(4096, 1024, 6144) == "void spmm::spmm_rowtile_mfma<128, 16, 4, 2, 1, 0>(spmm::KernelArgs)"
     assert plan(768, 768, 128, 0.9, (128, 8)) == (128, 128, 6)
 
     # 4-byte outputs: workgroups of 12 or 8 compute waves plus 4 loader waves
@@ -359,3 +359,28 @@ def test_pack_ex_rejects_unknown_flags():
     h = ctypes.c_void_p()
     rc = sp.lib().spmm_pack_ex(W.ctypes.data_as(ctypes.c_void_p), 8, 8, 8, 0, 4, ctypes.byref(h))
     assert rc == 1 and not h.value
+
+
+def test_binding_refuses_buffers_smaller_than_the_call_touches():
+    """Marshalling-side guard: a tensor built for another shape raises in Python instead of reaching the device."""
+    torch = pytest.importorskip("torch")
+    h = sp.spmm_pack_host(wl.sparse_weight(256, 256, 0.9, keys=(85,)))
+    try:
+        ep = sp.make_epilogue(None, 1.0, 0, None, "none", "s8", 1.0, 0, 1.0, None)
+        X = torch.zeros((256, 128), dtype=torch.uint8)
+        small = torch.zeros((64, 128), dtype=torch.int8)
+        for fn, args in ((sp.spmm_run, (h, X, 128, 128, ep, small, 128)), (sp.spmm_run_bound, (h, X, 128, 128, ep, small, 128)),
+                         (sp.spmm_run_tiled, (h, X, 128, 128, ep, small, 128, 3)),
+                         (sp.spmm_run_tiled_bound, (h, torch.zeros((100, 128), dtype=torch.uint8), 128, 128, ep,
+                                                    torch.zeros((256, 128), dtype=torch.int8), 128, 1))):
+            with pytest.raises(ValueError):
+                fn(*args)
+        # a view into a larger storage counts from its own offset; a sufficient one reaches the library
+        # (which refuses this host-only handle)
+        big = torch.zeros(256 * 128 + 64, dtype=torch.int8)
+        with pytest.raises(sp.SpmmError):
+            sp.spmm_run(h, X, 128, 128, ep, big[64:].view(256, 128), 128)
+        with pytest.raises(ValueError):
+            sp.spmm_run(h, X, 128, 128, ep, big[65:], 128)
+    finally:
+        sp.spmm_destroy(h)
