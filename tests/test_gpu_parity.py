@@ -644,8 +644,11 @@ def test_tile_major_large_case_and_argument_errors():
         ep = sp.make_epilogue(None, 1.0, 0, None, "none", "s32", 1.0, 0, 1.0, None)
         Xt = dev(sp.tile_major(d["X"]))
         out = torch.zeros((256, 128), dtype=torch.int32, device="cuda")
+        shifted = torch.zeros(Xt.numel() + 16, dtype=torch.uint8, device="cuda")[1:]
         with pytest.raises(sp.SpmmError):                        # activations must be 16-byte aligned
-            sp.spmm_run_tiled(h, Xt.view(-1)[1:], 100, 0, ep, out, 128, sp.binding.SPMM_TILED_X, None)
+            sp.spmm_run_tiled(h, shifted, 100, 0, ep, out, 128, sp.binding.SPMM_TILED_X, None)
+        with pytest.raises(ValueError):                          # ... and large enough (checked by the binding)
+            sp.spmm_run_tiled(h, Xt.view(-1)[16:], 100, 0, ep, out, 128, sp.binding.SPMM_TILED_X, None)
     finally:
         sp.spmm_destroy(h)
 
