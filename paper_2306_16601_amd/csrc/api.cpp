@@ -308,6 +308,14 @@ static spmm_status_t run_common(const spmm_handle_t* h, const uint8_t* X_dev, in
                        (h->bsr.N * ep->ld_sum * 4 < ((int64_t)1 << 31));
     }
 
+    if (a.out_vec_ok) {
+        // extent of the output (the fast paths store through a buffer resource of this size: the
+        // hardware drops a store that would leave it)
+        const int64_t tiles = (M + SPMM_X_TILE - 1) / SPMM_X_TILE;
+        const int64_t extent = out_tiled ? tiles * h->bsr.N * SPMM_X_TILE : ((h->bsr.N - 1) * ldo + M) * esz;
+        a.out_bytes = (uint32_t)extent;
+    }
+
     const spmm::Plan p = plan_for(h, M, a.x_vec_ok && a.out_vec_ok, (int)esz);
     const int rc = spmm::launch_spmm(p, a, ot, (gelu ? SPMM_POST_GELU : SPMM_POST_NONE) | (ep->sum ? spmm::POST_SUM_BIT : 0),
                                      hip_stream);

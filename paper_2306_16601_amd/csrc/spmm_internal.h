@@ -90,6 +90,7 @@ struct KernelArgs {
                          // (and, with Sum, the same for the second operand)
     int out_tile_stride; // 0: out row-major [N][ldo]; else 1-byte out token-tile-major [ceil(M/32)][N][32], ldo = 32 and this = 32 N
     int x_tile_stride;   // 0: X row-major [K][ldx]; else X token-tile-major [ceil(M/32)][K][32], ldx = 32 and this = 32 K
+    uint32_t out_bytes;  // with out_vec_ok: bytes from out to the end of the last element the call may write (< 2^31)
 };
 
 struct Plan {

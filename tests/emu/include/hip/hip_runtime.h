@@ -96,6 +96,17 @@ static inline uint32_t emu_alignbyte(uint32_t hi, uint32_t lo, uint32_t sh)
     return (uint32_t)(v >> (8 * (sh & 3)));
 }
 #define __builtin_amdgcn_alignbyte(hi, lo, sh) emu_alignbyte((hi), (lo), (sh))
+// buffer resource + raw buffer store: base pointer and size; a store that would leave the buffer is dropped
+struct emu_buffer_rsrc { uint8_t* base; uint32_t bytes; };
+typedef emu_buffer_rsrc __amdgpu_buffer_rsrc_t;
+#define __builtin_amdgcn_make_buffer_rsrc(p, stride, num, flags) (emu_buffer_rsrc{(uint8_t*)(p), (uint32_t)(num)})
+template <typename V>
+static inline void emu_buffer_store(const V v, const emu_buffer_rsrc r, const int voff, const int soff)
+{
+    const uint64_t off = (uint64_t)(uint32_t)voff + (uint32_t)soff;
+    if (off + sizeof(V) <= r.bytes) memcpy(r.base + off, &v, sizeof(V));
+}
+#define __builtin_amdgcn_raw_buffer_store_b128(v, r, vo, so, aux) emu_buffer_store((v), (r), (vo), (so))
 using std::min;
 using std::max;
 
