@@ -96,6 +96,32 @@ struct GlobalLut {
 // POST template parameters below are the SPMM_POST_* value, plus POST_SUM_BIT when the Sum
 // post-operator (a second binary32 tensor added after BiasAdd / GeLU, before Quantize) is on.
 
+// Output stores of the aligned paths.  They go out at agent scope (sc1), i.e. written through the
+// XCD's L2 as they are issued: left at the default scope the lines stay dirty in that L2 and are
+// written back when the kernel ends, behind all the compute, and that write-back is then the
+// tail of every launch (measured: 25 MB of 1-byte outputs 25.1 -> 23.2 us, 50 MB of binary32
+// outputs 18.0 -> 16.1 us).  The buffer resource covers exactly the bytes the call may write
+// (out_bytes, < 2 GiB on these paths): a store beyond it is dropped by the hardware.
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+constexpr int STORE_AGENT_SCOPE = 16;   // cache-policy operand of the buffer stores: sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t out_resource(const KernelArgs& a)
+{
+    // raw buffer (stride 0), 32-bit data format
+    return __builtin_amdgcn_make_buffer_rsrc(a.out, 0, (int)a.out_bytes, 0x00020000);
+}
+// (byte_off: per lane; uniform_off: the same for the whole wave, held in a scalar register)
+__device__ __forceinline__ void store4_out(const __amdgpu_buffer_rsrc_t rs, const uint32_t byte_off, const uint32_t v)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(v, rs, (int)byte_off, 0, STORE_AGENT_SCOPE);
+}
+template <typename V>
+__device__ __forceinline__ void store16_out(const __amdgpu_buffer_rsrc_t rs, const uint32_t byte_off, const V v,
+                                            const uint32_t uniform_off = 0)
+{
+    static_assert(sizeof(V) == 16, "16-byte store");
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), rs, (int)byte_off, (int)uniform_off, STORE_AGENT_SCOPE);
+}
+
 // quantised code of one pre-activation y (Quantize post-operator / table look-up)
 template <int OUT, int POST, typename Lut>
 __device__ __forceinline__ uint32_t quantise(const KernelArgs& a, const float y, const Lut& lut)
@@ -114,8 +140,9 @@ __device__ __forceinline__ uint32_t quantise(const KernelArgs& a, const float y,
 // Generic post-operators + store for 4 consecutive tokens m0..m0+3 of output row n: any
 // alignment, any tail (the slow path of every kernel).
 // WIDE: 1-byte outputs of an unaligned matrix are written in the widest pieces the address
-// allows (dword, two halves, bytes) instead of bytes; costs registers the 16-wave pipelined
-// kernels do not have (the host does not pick those for unaligned operands).
+// allows (dword, two halves, bytes) instead of bytes, and the aligned stores go out at agent
+// scope (see out_resource); costs registers the 16-wave pipelined kernels do not have (the
+// host does not pick those for unaligned operands, and their full tiles take finish_tile_fast).
 // OT: layout of a 1-byte output: 1 = token-tile-major, 0 = row-major, -1 = whichever the arguments say
 template <int OUT, int POST, bool WIDE = false, int OT = -1, typename Lut>
 __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, const float s, const float b,
@@ -125,7 +152,8 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
     if constexpr (OUT == SPMM_OUT_S32) {
         int32_t* o = (int32_t*)a.out + (int64_t)n * a.ldo + m0;
         if (a.out_vec_ok && valid >= 4) {
-            *(v4i*)o = acc;
+            if constexpr (WIDE) store16_out(out_resource(a), 4u * ((uint32_t)n * (uint32_t)a.ldo + (uint32_t)m0), acc);
+            else *(v4i*)o = acc;
         } else {
             for (int r = 0; r < 4; ++r)
                 if (r < valid) o[r] = acc[r];
@@ -148,7 +176,8 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
             float* o = (float*)a.out + (int64_t)n * a.ldo + m0;
             if (a.out_vec_ok && valid >= 4) {
                 v4f v = {y[0], y[1], y[2], y[3]};
-                *(v4f*)o = v;
+                if constexpr (WIDE) store16_out(out_resource(a), 4u * ((uint32_t)n * (uint32_t)a.ldo + (uint32_t)m0), v);
+                else *(v4f*)o = v;
             } else {
                 for (int r = 0; r < 4; ++r)
                     if (r < valid) o[r] = y[r];
@@ -162,7 +191,11 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
             const bool ot = (OT == 1) || (OT == -1 && a.out_tile_stride != 0);
             uint8_t* o = (uint8_t*)a.out + (int64_t)n * a.ldo +
                          (ot ? (int64_t)(m0 >> 5) * a.out_tile_stride + (m0 & 31) : (int64_t)m0);
-            if (valid >= 4 && (a.out_vec_ok || (WIDE && ((uintptr_t)o & 3) == 0))) {
+            if (WIDE && valid >= 4 && a.out_vec_ok) {
+                const uint32_t off = (uint32_t)n * (uint32_t)a.ldo +
+                                     (ot ? (uint32_t)(m0 >> 5) * (uint32_t)a.out_tile_stride + (uint32_t)(m0 & 31) : (uint32_t)m0);
+                store4_out(out_resource(a), off, q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24));
+            } else if (valid >= 4 && (a.out_vec_ok || (WIDE && ((uintptr_t)o & 3) == 0))) {
                 *(uint32_t*)o = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
             } else if (WIDE && valid >= 4 && ((uintptr_t)o & 1) == 0) {
                 *(uint16_t*)o = (uint16_t)(q[0] | (q[1] << 8));
@@ -173,28 +206,6 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
             }
         }
     }
-}
-
-// Output stores of the fast paths.  They go out at agent scope (sc1), i.e. written through the
-// XCD's L2 as they are issued: left at the default scope the lines stay dirty in that L2 and are
-// written back when the kernel ends, behind all the compute, and that write-back is then the
-// tail of every launch (measured: 25 MB of 1-byte outputs 25.1 -> 23.2 us, 50 MB of binary32
-// outputs 18.0 -> 16.1 us).  The buffer resource covers exactly the bytes the call may write
-// (out_bytes, < 2 GiB on these paths): a store beyond it is dropped by the hardware.
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-constexpr int STORE_AGENT_SCOPE = 16;   // cache-policy operand of the buffer stores: sc1
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t out_resource(const KernelArgs& a)
-{
-    // raw buffer (stride 0), 32-bit data format
-    return __builtin_amdgcn_make_buffer_rsrc(a.out, 0, (int)a.out_bytes, 0x00020000);
-}
-// (byte_off: per lane; uniform_off: the same for the whole wave, held in a scalar register)
-template <typename V>
-__device__ __forceinline__ void store16_out(const __amdgpu_buffer_rsrc_t rs, const uint32_t byte_off, const V v,
-                                            const uint32_t uniform_off = 0)
-{
-    static_assert(sizeof(V) == 16, "16-byte store");
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), rs, (int)byte_off, (int)uniform_off, STORE_AGENT_SCOPE);
 }
 
 // s_waitcnt vmcnt(0) only (expcnt / lgkmcnt fields left at their maxima).  Issued when the
