@@ -96,30 +96,31 @@ struct GlobalLut {
 // POST template parameters below are the SPMM_POST_* value, plus POST_SUM_BIT when the Sum
 // post-operator (a second binary32 tensor added after BiasAdd / GeLU, before Quantize) is on.
 
-// Output stores of the aligned paths.  They go out at agent scope (sc1), i.e. written through the
-// XCD's L2 as they are issued: left at the default scope the lines stay dirty in that L2 and are
-// written back when the kernel ends, behind all the compute, and that write-back is then the
-// tail of every launch (measured: 25 MB of 1-byte outputs 25.1 -> 23.2 us, 50 MB of binary32
-// outputs 18.0 -> 16.1 us).  The buffer resource covers exactly the bytes the call may write
-// (out_bytes, < 2 GiB on these paths): a store beyond it is dropped by the hardware.
+// Output stores of the aligned paths go through a buffer resource that covers exactly the bytes
+// the call may write (out_bytes, < 2 GiB on these paths): a store beyond it is dropped by the
+// hardware.  Where one store instruction of a wave fills whole 128-byte lines (1-byte outputs in
+// token-tile-major order: 16 rows x 32 bytes back to back) or the output is 4 bytes wide, the
+// store goes out at agent scope (sc1), i.e. written through the XCD's L2 as it is issued: left at
+// the default scope the lines stay dirty in that L2 and are written back when the kernel ends,
+// behind all the compute, and that write-back is then the tail of every launch (measured inside
+// the rotating benchmark step, outputs going to HBM: 4096 x 1024 at 90 %, 24.8 -> 23.1 us; binary32
+// 3072 x 768, 18.4 -> 17.2 us).  Row-major 1-byte outputs leave in 64-byte runs, half a line per
+// instruction; written through, those cost more at the memory than they save (25.0 -> 27.3 us),
+// so they stay at the default scope and the L2 merges them.
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-constexpr int STORE_AGENT_SCOPE = 16;   // cache-policy operand of the buffer stores: sc1
+constexpr int SCOPE_DEFAULT = 0, SCOPE_AGENT = 16;   // cache-policy operand of the buffer stores: none / sc1
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t out_resource(const KernelArgs& a)
 {
     // raw buffer (stride 0), 32-bit data format
     return __builtin_amdgcn_make_buffer_rsrc(a.out, 0, (int)a.out_bytes, 0x00020000);
 }
 // (byte_off: per lane; uniform_off: the same for the whole wave, held in a scalar register)
-__device__ __forceinline__ void store4_out(const __amdgpu_buffer_rsrc_t rs, const uint32_t byte_off, const uint32_t v)
-{
-    __builtin_amdgcn_raw_buffer_store_b32(v, rs, (int)byte_off, 0, STORE_AGENT_SCOPE);
-}
-template <typename V>
+template <int SCOPE, typename V>
 __device__ __forceinline__ void store16_out(const __amdgpu_buffer_rsrc_t rs, const uint32_t byte_off, const V v,
                                             const uint32_t uniform_off = 0)
 {
     static_assert(sizeof(V) == 16, "16-byte store");
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), rs, (int)byte_off, (int)uniform_off, STORE_AGENT_SCOPE);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, v), rs, (int)byte_off, (int)uniform_off, SCOPE);
 }
 
 // quantised code of one pre-activation y (Quantize post-operator / table look-up)
@@ -140,7 +141,7 @@ __device__ __forceinline__ uint32_t quantise(const KernelArgs& a, const float y,
 // Generic post-operators + store for 4 consecutive tokens m0..m0+3 of output row n: any
 // alignment, any tail (the slow path of every kernel).
 // WIDE: 1-byte outputs of an unaligned matrix are written in the widest pieces the address
-// allows (dword, two halves, bytes) instead of bytes, and the aligned stores go out at agent
+// allows (dword, two halves, bytes) instead of bytes, and aligned 4-byte outputs go out at agent
 // scope (see out_resource); costs registers the 16-wave pipelined kernels do not have (the
 // host does not pick those for unaligned operands, and their full tiles take finish_tile_fast).
 // OT: layout of a 1-byte output: 1 = token-tile-major, 0 = row-major, -1 = whichever the arguments say
@@ -152,7 +153,7 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
     if constexpr (OUT == SPMM_OUT_S32) {
         int32_t* o = (int32_t*)a.out + (int64_t)n * a.ldo + m0;
         if (a.out_vec_ok && valid >= 4) {
-            if constexpr (WIDE) store16_out(out_resource(a), 4u * ((uint32_t)n * (uint32_t)a.ldo + (uint32_t)m0), acc);
+            if constexpr (WIDE) store16_out<SCOPE_AGENT>(out_resource(a), 4u * ((uint32_t)n * (uint32_t)a.ldo + (uint32_t)m0), acc);
             else *(v4i*)o = acc;
         } else {
             for (int r = 0; r < 4; ++r)
@@ -176,7 +177,7 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
             float* o = (float*)a.out + (int64_t)n * a.ldo + m0;
             if (a.out_vec_ok && valid >= 4) {
                 v4f v = {y[0], y[1], y[2], y[3]};
-                if constexpr (WIDE) store16_out(out_resource(a), 4u * ((uint32_t)n * (uint32_t)a.ldo + (uint32_t)m0), v);
+                if constexpr (WIDE) store16_out<SCOPE_AGENT>(out_resource(a), 4u * ((uint32_t)n * (uint32_t)a.ldo + (uint32_t)m0), v);
                 else *(v4f*)o = v;
             } else {
                 for (int r = 0; r < 4; ++r)
@@ -191,11 +192,7 @@ __device__ __forceinline__ void finish4(const KernelArgs& a, const v4i acc, cons
             const bool ot = (OT == 1) || (OT == -1 && a.out_tile_stride != 0);
             uint8_t* o = (uint8_t*)a.out + (int64_t)n * a.ldo +
                          (ot ? (int64_t)(m0 >> 5) * a.out_tile_stride + (m0 & 31) : (int64_t)m0);
-            if (WIDE && valid >= 4 && a.out_vec_ok) {
-                const uint32_t off = (uint32_t)n * (uint32_t)a.ldo +
-                                     (ot ? (uint32_t)(m0 >> 5) * (uint32_t)a.out_tile_stride + (uint32_t)(m0 & 31) : (uint32_t)m0);
-                store4_out(out_resource(a), off, q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24));
-            } else if (valid >= 4 && (a.out_vec_ok || (WIDE && ((uintptr_t)o & 3) == 0))) {
+            if (valid >= 4 && (a.out_vec_ok || (WIDE && ((uintptr_t)o & 3) == 0))) {
                 *(uint32_t*)o = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
             } else if (WIDE && valid >= 4 && ((uintptr_t)o & 1) == 0) {
                 *(uint16_t*)o = (uint16_t)(q[0] | (q[1] << 8));
@@ -377,7 +374,7 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
         const __amdgpu_buffer_rsrc_t rs = out_resource(a);
         if (tile * TILE_ROWS + c < a.N) {
 #pragma unroll
-            for (int i = 0; i < G::PIECES; ++i) store16_out(rs, 4u * off + 64u * i, acc[i]);
+            for (int i = 0; i < G::PIECES; ++i) store16_out<SCOPE_AGENT>(rs, 4u * off + 64u * i, acc[i]);
         }
     } else if constexpr (OUT == SPMM_OUT_F32) {
         const uint32_t off = (uint32_t)(tile * TILE_ROWS + c) * (uint32_t)a.ldo + (uint32_t)(tok0 + 4 * g);
@@ -394,7 +391,7 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
                     if constexpr ((POST & SPMM_POST_GELU) != 0) y[r] = gelu_f32(y[r]);
                 }
                 if constexpr ((POST & POST_SUM_BIT) != 0) y = y + *(const v4f*)(sp + 16 * i);
-                store16_out(rs, 4u * off + 64u * i, y);
+                store16_out<SCOPE_AGENT>(rs, 4u * off + 64u * i, y);
             }
         }
     } else {
@@ -437,7 +434,16 @@ __device__ __forceinline__ void finish_tile_fast(const KernelArgs& a, const v4i 
                 *(uint32_t*)(lds + wbase + (uint32_t)(j ^ wsw) * G::STRIDE) = word;
             }
             const v4i v = *(const v4i*)(lds + raddr);   // same wave: LDS operations complete in order
-            if (orow < a.N && 4 * h + rj < G::PIECES) store16_out(rs, off, v, half_step * h);
+            if (orow < a.N && 4 * h + rj < G::PIECES) {
+                if constexpr (OT == 1) {
+                    store16_out<SCOPE_AGENT>(rs, off, v, half_step * h);
+                } else if constexpr (OT == 0) {
+                    *(v4i*)((uint8_t*)a.out + off + half_step * h) = v;
+                } else {
+                    if (ot) store16_out<SCOPE_AGENT>(rs, off, v, half_step * h);
+                    else store16_out<SCOPE_DEFAULT>(rs, off, v, half_step * h);
+                }
+            }
         }
     }
 }

@@ -107,7 +107,6 @@ static inline void emu_buffer_store(const V v, const emu_buffer_rsrc r, const in
     if (off + sizeof(V) <= r.bytes) memcpy(r.base + off, &v, sizeof(V));
 }
 #define __builtin_amdgcn_raw_buffer_store_b128(v, r, vo, so, aux) emu_buffer_store((v), (r), (vo), (so))
-#define __builtin_amdgcn_raw_buffer_store_b32(v, r, vo, so, aux) emu_buffer_store((uint32_t)(v), (r), (vo), (so))
 using std::min;
 using std::max;
 
