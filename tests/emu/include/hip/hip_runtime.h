@@ -96,7 +96,8 @@ static inline uint32_t emu_alignbyte(uint32_t hi, uint32_t lo, uint32_t sh)
     return (uint32_t)(v >> (8 * (sh & 3)));
 }
 #define __builtin_amdgcn_alignbyte(hi, lo, sh) emu_alignbyte((hi), (lo), (sh))
-// buffer resource + raw buffer store: base pointer and size; a store that would leave the buffer is dropped
+// buffer resource + raw buffer store: base pointer and size.  The hardware drops a store that would leave the
+// buffer; the kernels never rely on that, so here it ends the run with a message
 struct emu_buffer_rsrc { uint8_t* base; uint32_t bytes; };
 typedef emu_buffer_rsrc __amdgpu_buffer_rsrc_t;
 #define __builtin_amdgcn_make_buffer_rsrc(p, stride, num, flags) (emu_buffer_rsrc{(uint8_t*)(p), (uint32_t)(num)})
@@ -104,7 +105,12 @@ template <typename V>
 static inline void emu_buffer_store(const V v, const emu_buffer_rsrc r, const int voff, const int soff)
 {
     const uint64_t off = (uint64_t)(uint32_t)voff + (uint32_t)soff;
-    if (off + sizeof(V) <= r.bytes) memcpy(r.base + off, &v, sizeof(V));
+    if (off + sizeof(V) > r.bytes) {
+        fprintf(stderr, "emu: buffer store of %zu bytes at offset %llu leaves the buffer of %u bytes\n", sizeof(V),
+                (unsigned long long)off, r.bytes);
+        abort();
+    }
+    memcpy(r.base + off, &v, sizeof(V));
 }
 #define __builtin_amdgcn_raw_buffer_store_b128(v, r, vo, so, aux) emu_buffer_store((v), (r), (vo), (so))
 using std::min;
