@@ -202,7 +202,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "mini_chain", "large_sum", "grid", "clustered"],
+    ap.add_argument("--workload", default="large", choices=["large", "base", "mini", "mini_chain", "large_chain", "large_sum", "grid", "clustered"],
                     help="large_sum: the two BERT-Large Linears that feed a residual add (attention output and "
                          "second feed-forward), with the Sum post-operator and fp32 output; mini_chain: the BERT-Mini "
                          "feed-forward pair chained on the device (GELU -> uint8 code of launch 1 is the activation "
@@ -268,13 +268,16 @@ def main() -> int:
     elif args.workload == "mini_chain":
         cases = wl.chain_cases()
         wname = "bert_mini_ffn_pair_chained_u8_m1024_s80"
+    elif args.workload == "large_chain":
+        cases = wl.chain_cases(large=True)
+        wname = "bert_large_ffn_pair_chained_u8_m6144_s90"
     elif args.workload == "clustered":
         cases = wl.clustered_cases()
         wname = "clustered32_4096x1024_m6144_s90_s80_gelu_s8"
     else:
         cases = wl.mini_cases()
         wname = "bert_mini_ffn_pair_m1024_s80"
-    made = wl.make_chain(cases) if args.workload == "mini_chain" else None
+    made = wl.make_chain(cases) if args.workload in ("mini_chain", "large_chain") else None
     if args.reorder:
         wname += "[rows reordered]"
     if args.only:

@@ -700,10 +700,13 @@ def test_tile_major_output(N, K, M, s, out_type, postop, x_tiled, tuning):
     assert_parity(got, oracle_spmm(d["W"], d["X"], d, case), case)
 
 
-def test_chained_ffn_pair_in_tile_major_order():
+@pytest.mark.parametrize("large", [False, True])
+def test_chained_ffn_pair_in_tile_major_order(large):
     """The chained pair of Section 3.3 with every activation tile-major: layer 1 reads tile-major X and writes its
-    u8 code tile-major, layer 2 reads that buffer as is; both bit-equal to the oracle chained the same way."""
-    c1, c2 = wl.chain_cases()
+    u8 code tile-major, layer 2 reads that buffer as is; both bit-equal to the oracle chained the same way.
+    large: at the feed-forward shapes and token count of BERT-Large (the pipelined kernels, whose tile-major
+    1-byte stores go out at agent scope, feeding each other)."""
+    c1, c2 = wl.chain_cases(large=large)
     d1, d2 = wl.make_chain([c1, c2])
     M = c1.M
     ref1 = oracle_spmm(d1["W"], d1["X"], d1, c1)

@@ -234,10 +234,19 @@ def mini_cases(orientation: str = N4K1) -> List[Case]:
     ]
 
 
-def chain_cases(orientation: str = N4K1) -> List[Case]:
+def chain_cases(orientation: str = N4K1, large: bool = False) -> List[Case]:
     """Config 2 as a chained pair (Figure 3 / Algorithm 2: a quantised operator feeding the next one with
     no fp32 tensor between them): W1 bias + GELU -> uint8 code with a zero point (the table chain), whose
-    output IS the activation matrix of W2 -> int8.  Inputs of the pair come from make_chain()."""
+    output IS the activation matrix of W2 -> int8.  Inputs of the pair come from make_chain().
+    large: the same pair with the feed-forward shapes and token count of config 4 (BERT-Large, 90 %)."""
+    if large:
+        M = 16 * 384
+        return [
+            Case("chain_ffn1_4096x1024_m%d_s90" % M, 4096, 1024, M, 0.90, orientation, OUT_U8,
+                 POST_GELU, keys=(7, 4096, 1024, M, 90)),
+            Case("chain_ffn2_1024x4096_m%d_s90" % M, 1024, 4096, M, 0.90, orientation, OUT_S8,
+                 POST_NONE, keys=(7, 1024, 4096, M, 90)),
+        ]
     M = 8 * 128
     return [
         Case("chain_ffn1_1024x256_m1024_s80", 1024, 256, M, 0.80, orientation, OUT_U8,
